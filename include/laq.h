@@ -1,0 +1,204 @@
+/*
+ * laq.h -- C ABI of the LAQ hot path for AMD Instinct MI355X (gfx950).
+ *
+ * LAQ = Lazily Aggregated Quantized gradients (Sun, Chen, Giannakis, Yang,
+ * NeurIPS 2019).  All M workers of the paper's worker-server protocol are
+ * simulated on one GPU.  One iteration of Algorithm 2 is three calls:
+ *
+ *     laq_worker_grads   g_m = grad f_m(theta^k)                (Alg. 2, worker step)
+ *     laq_quantize_skip  (R_m, q_m), upload mask                 (eqs. 5-7)
+ *     laq_server_step    nabla^k, theta^{k+1}, stored Q_m        (eq. 4)
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory, every other pointer is HOST
+ *    memory.  The library never allocates or frees device memory: state lives
+ *    in a caller-provided workspace that must stay alive until laq_destroy.
+ *  - All device pointers must be 16-byte aligned.  Per-worker vectors are
+ *    rows of a matrix with row stride laq_p_stride(p) floats (gradients,
+ *    stored quantized gradients) or laq_w_stride(p, b) 32-bit words (codes).
+ *    Padding elements are never read into a result.
+ *  - All work is enqueued on the HIP stream given to laq_create; the three
+ *    hot calls never synchronise with the host.
+ *  - Every call returns a laq_status.  LAQ_EDEVICE means a HIP call failed;
+ *    laq_last_error() describes it.  No exception crosses this boundary.
+ *  - A context is not thread-safe; calls on one context that overlap in time
+ *    (from different host threads or streams) race on its workspace.
+ *
+ * Finite precision (the paper states its formulas over the reals): codes,
+ * radii and upload decisions are a deterministic function of the gradients
+ * and the state.  Elementwise steps are single IEEE binary32 operations in
+ * the order documented at laq_quantize_skip; the two squared norms that
+ * decide an upload are accumulated as exact integers, so they do not depend
+ * on the reduction order.
+ */
+#ifndef LAQ_H
+#define LAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct laq_ctx laq_ctx;
+
+typedef enum laq_status {
+  LAQ_OK = 0,
+  LAQ_EINVAL = 1,     /* bad argument (null, range, alignment, size)          */
+  LAQ_ESTATE = 2,     /* call order: e.g. worker_grads without model and data */
+  LAQ_EDEVICE = 3,    /* a HIP runtime call failed                             */
+  LAQ_ENONFINITE = 4  /* a radius R_m was inf/NaN (reported by get_counters)  */
+} laq_status;
+
+typedef enum laq_model_kind {
+  LAQ_MODEL_NONE = 0,    /* caller supplies the gradients                      */
+  LAQ_MODEL_BINLOG = 1,  /* binary logistic loss, dims = {F}                   */
+  LAQ_MODEL_SOFTMAX = 2, /* multinomial logistic regression, dims = {F, C}     */
+  LAQ_MODEL_MLP = 3      /* fully connected ReLU net, dims = layer widths      */
+} laq_model_kind;
+
+/* laq_set_mode flags */
+#define LAQ_MODE_FORCE_UPLOAD 1u /* every worker uploads every round: Algorithm 1 (QGD) */
+
+#define LAQ_MAX_BITS 16
+#define LAQ_MAX_LAYERS 8
+
+/* Row stride, in floats, of per-worker gradient matrices (p rounded up to a
+ * multiple of 4). */
+int64_t laq_p_stride(int64_t p);
+
+/* Row stride, in 32-bit words, of the packed code matrix.  Codes of one
+ * worker form one LSB-first bitstream over little-endian words: code i sits at
+ * bit offset i*b (the 32 + b*p bit message of Sec. 2.1 is this stream plus
+ * R_m).  The stride covers ceil(p/8)*b bytes rounded up to 16 bytes; bits
+ * past code p-1 inside the first ceil(p*b/32) words are written as zero. */
+int64_t laq_w_stride(int64_t p, int32_t b);
+
+/* Bytes of device workspace laq_create needs for these sizes. */
+size_t laq_workspace_bytes(int32_t M, int64_t p, int32_t b, int32_t D);
+
+/*
+ * Algorithm 2, lines 1-2.  M workers, p parameters, b bits per coordinate
+ * (1..16), D past parameter differences weighted by xi[0..D-1] (host array,
+ * xi[d-1] = xi_d >= 0), clock limit t_bar >= D, step size alpha > 0.
+ * workspace_dev: at least laq_workspace_bytes(M,p,b,D) bytes, 256-byte
+ * aligned, owned by the caller.  hip_stream: a hipStream_t (NULL = the
+ * default stream).  Initial state (the paper leaves it open): stored
+ * quantized gradients 0, nabla 0, ||eps_hat||^2 = 0, parameter-difference
+ * history 0, clocks t_m = t_bar so the first iteration is a full round.
+ * On success *out owns a small host object; free it with laq_destroy.
+ */
+int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D,
+               const float* xi, int32_t t_bar, float alpha, void* workspace_dev,
+               size_t workspace_bytes, void* hip_stream);
+
+int laq_destroy(laq_ctx* ctx);
+
+/* Back to the initial state of laq_create (enqueued on the stream). */
+int laq_reset(laq_ctx* ctx);
+
+int laq_set_mode(laq_ctx* ctx, uint32_t flags);
+
+/*
+ * Models of the supplement ("Simulation details").  The global loss is the
+ * mean over all N = M*N_m samples of cross-entropy + (lambda/2)||theta||^2, so
+ * worker m's gradient is (1/N) sum_n grad CE_n + (N_m/N) lambda theta.
+ *   BINLOG : dims = {F};      theta[F];    labels in {-1,+1}
+ *   SOFTMAX: dims = {F, C};   theta[C][F]; P = softmax(theta x); labels 0..C-1
+ *   MLP    : dims = {d_0..d_L}, 2 <= L+1 <= LAQ_MAX_LAYERS+1; theta is
+ *            (W_1[d_0][d_1], b_1[d_1], W_2, b_2, ...) flattened, ReLU between
+ *            layers, softmax cross-entropy on the last.
+ * The parameter count implied by dims must equal p.
+ */
+int laq_set_model(laq_ctx* ctx, int32_t kind, const int32_t* dims, int32_t n_dims,
+                  float lambda);
+
+/* Bytes of device scratch (activations, partial sums) the model needs for
+ * N_m samples per worker; 0 if no model is set. */
+size_t laq_model_workspace_bytes(const laq_ctx* ctx, int64_t N_m);
+
+/*
+ * Training data, caller-owned, device memory: X_dev[M][N_m][ldx] row-major
+ * fp32 with ldx >= dims[0], ldx % 4 == 0 (columns past dims[0] are ignored);
+ * y_dev[M][N_m] int32.  model_ws_dev: laq_model_workspace_bytes(ctx, N_m)
+ * bytes of scratch, 256-byte aligned, caller-owned, alive while used.
+ */
+int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t N_m,
+                 int64_t ldx, void* model_ws_dev, size_t model_ws_bytes);
+
+/*
+ * Algorithm 2, worker step, first half: G_dev[m][0..p) = grad f_m(theta) for
+ * all M workers (fp32 arithmetic; row stride laq_p_stride(p)).
+ * theta_dev[p] is read only.  Needs laq_set_model and laq_set_data.
+ */
+int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev);
+
+/*
+ * Innovation quantizer (Sec. 2.1, eqs. 5-6) and skip rule (Sec. 2.2, eqs.
+ * 7a-7b) for all workers.  With h_m the stored quantized gradient, L = 2^b-1,
+ * and (+),(-),(*),(/) single binary32 operations:
+ *     d_i = g_i (-) h_i              R_m = max_i |d_i|
+ *     s = L (/) (2 (*) R_m)          step = (2 (*) R_m) (/) L
+ *     q_i = clamp(floor(((d_i (+) R_m) (*) s) (+) 0.5), 0, L)
+ *     delta_i = (q_i (*) step) (-) R_m     eps_i = g_i (-) (h_i (+) delta_i)
+ * R_m == 0 (or s not finite) gives q = 0, delta = 0.  The worker skips iff
+ *     (R_m/L)^2 sum_i (2 q_i - L)^2  <=  (1/(alpha^2 M^2)) sum_d xi_d dtheta2[d]
+ *                                         + 3 (||eps_m||^2 + ||eps_hat_m||^2)
+ * and t_m < t_bar (binary64, fixed order), where ||eps_m||^2 is the exact
+ * integer sum of rint(eps_i 2^(K-x))^2 scaled by 2^(2(x-K)), 2^(x-1) <= step <
+ * 2^x, K = min(20, floor((63 - ceil(log2 p))/2)).
+ * Outputs (the "messages"): codes_dev[M][laq_w_stride], R_dev[M],
+ * upload_dev[M] (1 = upload, 0 = skip).  Codes and R are written for every
+ * worker.  Internal state is not modified except the per-call stash read by
+ * laq_server_step, so the call may be repeated.
+ */
+int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev,
+                      float* R_dev, uint8_t* upload_dev);
+
+/*
+ * Server update (eq. 4) and the bookkeeping of Algorithm 2: for workers with
+ * upload_dev[m] = 1, in ascending m: delta from (R_m, q_m), stored
+ * Q_m += delta, acc_i += delta_i, ||eps_hat_m||^2 = ||eps_m||^2, t_m = 0,
+ * uploads_m += 1, bits += 32 + b p; other workers: t_m += 1.  Then
+ * nabla_i += acc_i, theta_i -= alpha * nabla_i, and alpha^2 ||nabla||^2 is
+ * pushed into the parameter-difference history.  theta_dev[p] is updated in
+ * place.  Reads only rows of uploading workers.
+ */
+int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
+                    const uint8_t* upload_dev, float* theta_dev);
+
+/* Device pointers into the workspace (valid until laq_destroy).  The caller
+ * may read or overwrite them between calls with stream-ordered copies; this
+ * is how a checkpoint is saved, restored, or a reference state is imposed. */
+typedef struct laq_state_view {
+  float* H_dev;            /* [M][p_stride] stored Q_m(theta_hat_m)            */
+  float* nabla_dev;        /* [p_stride]                                       */
+  double* Ehat2_dev;       /* [M] ||eps_hat_m||^2                              */
+  int32_t* t_dev;          /* [M] clocks                                       */
+  double* dtheta2_dev;     /* [D] index 0 = most recent ||theta^{k+1}-theta^k||^2 */
+  int64_t* Sq_dev;         /* [M] last call's sum (2q-L)^2                     */
+  double* E2_dev;          /* [M] last call's ||eps_m||^2                      */
+  double* lhs_dev;         /* [M] last call's left side of (7a)                */
+  double* rhs_dev;         /* [M] last call's right side of (7a)               */
+  uint64_t* uploads_dev;   /* [M] upload counts                                */
+  uint64_t* bits_dev;      /* [1] total transmitted bits                       */
+  uint32_t* status_dev;    /* [1] nonzero once a radius was not finite         */
+  int64_t p_stride;
+  int64_t w_stride;
+} laq_state_view;
+
+int laq_get_state(laq_ctx* ctx, laq_state_view* view);
+
+/* Synchronises the stream and copies the counters to host arrays
+ * uploads[M], *bits_total.  Returns LAQ_ENONFINITE if any radius so far was
+ * not finite. */
+int laq_get_counters(laq_ctx* ctx, uint64_t* uploads, uint64_t* bits_total);
+
+/* Text of the last error on this context ("" if none); owned by the context. */
+const char* laq_last_error(const laq_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAQ_H */

@@ -1,0 +1,844 @@
+// LAQ hot path for gfx950: context, innovation quantizer + skip rule, lazy
+// aggregation + parameter update.  Algorithm 2 and eqs. 4-7 of Sun, Chen,
+// Giannakis, Yang, "Communication-Efficient Distributed Learning via Lazily
+// Aggregated Quantized Gradients".
+//
+// Data ownership per lane: 8 consecutive coordinates.  8 codes of b bits are
+// exactly b bytes, so every lane writes (or reads) a whole number of bytes of
+// the packed bitstream for any b and no cross-lane packing is needed; the two
+// 16-byte loads per operand keep every request 16-byte aligned.
+//
+// This file must be compiled with -ffp-contract=off: every elementwise step
+// below is one IEEE binary32 operation, in the documented order.
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "laq_internal.h"
+
+namespace laq {
+
+int set_error(laq_ctx* ctx, int status, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return status;
+}
+
+static inline int64_t round_up(int64_t a, int64_t m) { return (a + m - 1) / m * m; }
+
+static int32_t ceil_log2(int64_t n) {
+  int32_t c = 0;
+  while (((int64_t)1 << c) < n) ++c;
+  return c;
+}
+
+// ------------------------------------------------------------------ device helpers
+
+__device__ __forceinline__ uint32_t abs_bits(float d) { return __float_as_uint(d) & 0x7fffffffu; }
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    uint32_t o = (uint32_t)__shfl_xor((int)v, off);
+    v = v > o ? v : o;
+  }
+  return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += (unsigned long long)__shfl_xor((long long)v, off);
+  return v;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// Per-worker quantizer constants derived from the radius (eq. 5 denominators).
+struct QuantConst {
+  float R, s, step;
+  int x;        // 2^(x-1) <= step < 2^x
+  bool finite;  // R and 2R finite
+  bool zero;    // zero (or unrepresentably small) innovation: all codes 0, delta 0
+};
+
+template <int B>
+__device__ __forceinline__ QuantConst quant_const(uint32_t rbits) {
+  QuantConst c;
+  constexpr float Lf = (float)((1 << B) - 1);
+  c.R = __uint_as_float(rbits);
+  const float two_R = 2.0f * c.R;
+  c.finite = (rbits < 0x7f800000u) && (abs_bits(two_R) < 0x7f800000u);
+  // binary64 quotient of two binary32 values, rounded once more to binary32,
+  // equals the correctly rounded binary32 quotient (53 >= 2*24 + 2).
+  c.s = (float)((double)Lf / (double)two_R);
+  c.step = (float)((double)two_R / (double)Lf);
+  c.zero = !c.finite || c.R == 0.0f || !(abs_bits(c.s) < 0x7f800000u);
+  c.x = 0;
+  if (!c.zero) (void)frexpf(c.step, &c.x);
+  return c;
+}
+
+// ------------------------------------------------------------------ pass 1: radius
+
+// R_m = || g_m - h_m ||_inf (Sec. 2.1).  The maximum is taken on the raw
+// bits of |d| (order-free, exact, NaN > inf so a NaN is not lost).  Each block
+// leaves its partial maximum in Rpart[m][block]; the second pass combines them
+// (no same-address atomics: thousands of them serialise at the memory side).
+__global__ __launch_bounds__(kThreads) void radius_kernel(const float* __restrict__ G,
+                                                          const float* __restrict__ H, int64_t p,
+                                                          int64_t p_stride, int32_t m0, int32_t slots,
+                                                          uint32_t* __restrict__ Rpart) {
+  const int m = m0 + blockIdx.y;
+  const float* g = G + (int64_t)m * p_stride;
+  const float* h = H + (int64_t)m * p_stride;
+  const int64_t nfull = p / kGroup;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  uint32_t mx = 0;
+  for (int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x; grp < nfull; grp += stride) {
+    const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
+    const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
+    const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
+    uint32_t a = max(max(abs_bits(g0.x - h0.x), abs_bits(g0.y - h0.y)),
+                     max(abs_bits(g0.z - h0.z), abs_bits(g0.w - h0.w)));
+    uint32_t c = max(max(abs_bits(g1.x - h1.x), abs_bits(g1.y - h1.y)),
+                     max(abs_bits(g1.z - h1.z), abs_bits(g1.w - h1.w)));
+    mx = max(mx, max(a, c));
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    for (int64_t i = nfull * kGroup; i < p; ++i) mx = max(mx, abs_bits(g[i] - h[i]));
+
+  mx = wave_max_u32(mx);
+  __shared__ uint32_t sm[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    Rpart[(int64_t)m * slots + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
+}
+
+// ------------------------------------------------------------------ pass 2: codes + skip rule
+
+struct QuantArgs {
+  const float* G;
+  const float* H;
+  uint32_t* codes;
+  float* R_out;
+  uint8_t* upload;
+  DeviceScalars sc;
+  int64_t p, p_stride, w_stride;
+  int32_t M, D, t_bar, eps_K, slots, reverse;
+  float alpha;
+  uint32_t mode;
+};
+
+// One coordinate of eqs. 5-6 plus its contributions to the two squared norms.
+template <int B>
+__device__ __forceinline__ uint32_t quant_one(float g, float h, const QuantConst& c, int sh,
+                                              double& accN, unsigned long long& accS) {
+  constexpr int L = (1 << B) - 1;
+  const float d = g - h;
+  const float u = d + c.R;
+  float t = u * c.s;
+  t = t + 0.5f;
+  float qf = floorf(t);
+  qf = fminf(fmaxf(qf, 0.0f), (float)L);
+  const uint32_t qi = (uint32_t)qf;
+  float dq = qf * c.step;
+  dq = dq - c.R;
+  const float hn = h + dq;
+  const float e = g - hn;
+  const double nd = (double)rintf(ldexpf(e, sh));   // integer-valued, |nd| < 2^21
+  accN = fma(nd, nd, accN);                          // exact while accN < 2^53
+  const int cc = 2 * (int)qi - L;
+  accS += (unsigned long long)(uint32_t)(cc * cc);
+  return qi;
+}
+
+template <int B>
+__device__ __forceinline__ void store_group(uint8_t* out, unsigned __int128 v) {
+  if constexpr (B == 16) {
+    uint4 w;
+    w.x = (uint32_t)v; w.y = (uint32_t)(v >> 32); w.z = (uint32_t)(v >> 64); w.w = (uint32_t)(v >> 96);
+    *reinterpret_cast<uint4*>(out) = w;
+  } else if constexpr (B == 8) {
+    uint2 w;
+    w.x = (uint32_t)v; w.y = (uint32_t)(v >> 32);
+    *reinterpret_cast<uint2*>(out) = w;
+  } else if constexpr (B == 4) {
+    *reinterpret_cast<uint32_t*>(out) = (uint32_t)v;
+  } else if constexpr (B == 2) {
+    *reinterpret_cast<uint16_t*>(out) = (uint16_t)v;
+  } else {
+#pragma unroll
+    for (int k = 0; k < B; ++k) out[k] = (uint8_t)(v >> (8 * k));
+  }
+}
+
+template <int B>
+__device__ __forceinline__ unsigned __int128 load_group(const uint8_t* in) {
+  if constexpr (B == 16) {
+    const uint4 w = *reinterpret_cast<const uint4*>(in);
+    return (unsigned __int128)w.x | ((unsigned __int128)w.y << 32) | ((unsigned __int128)w.z << 64) |
+           ((unsigned __int128)w.w << 96);
+  } else if constexpr (B == 8) {
+    const uint2 w = *reinterpret_cast<const uint2*>(in);
+    return (unsigned __int128)w.x | ((unsigned __int128)w.y << 32);
+  } else if constexpr (B == 4) {
+    return *reinterpret_cast<const uint32_t*>(in);
+  } else if constexpr (B == 2) {
+    return *reinterpret_cast<const uint16_t*>(in);
+  } else {
+    unsigned __int128 v = 0;
+#pragma unroll
+    for (int k = 0; k < B; ++k) v |= (unsigned __int128)in[k] << (8 * k);
+    return v;
+  }
+}
+
+template <int B>
+__global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a, int32_t m0) {
+  constexpr int L = (1 << B) - 1;
+  // the second pass walks workers and coordinates in the opposite direction of
+  // the first, so it starts on the data the first pass touched last (still
+  // resident in the memory-side cache)
+  const int m = a.reverse ? m0 + (int)(gridDim.y - 1 - blockIdx.y) : m0 + (int)blockIdx.y;
+  const float* g = a.G + (int64_t)m * a.p_stride;
+  const float* h = a.H + (int64_t)m * a.p_stride;
+  uint8_t* out = reinterpret_cast<uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+  __shared__ uint32_t smR[kThreads / 64];
+  {
+    // radius of worker m from the first pass's block partials
+    uint32_t mx = 0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += kThreads)
+      mx = max(mx, a.sc.Rpart[(int64_t)m * a.slots + i]);
+    mx = wave_max_u32(mx);
+    if ((threadIdx.x & 63) == 0) smR[threadIdx.x >> 6] = mx;
+    __syncthreads();
+  }
+  const QuantConst c = quant_const<B>(max(max(smR[0], smR[1]), max(smR[2], smR[3])));
+  const int sh = a.eps_K - c.x;
+  const int64_t nfull = a.p / kGroup;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+
+  double accN = 0.0;
+  unsigned long long accS = 0;
+
+  if (c.zero) {
+    for (int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x; grp < nfull; grp += stride)
+      store_group<B>(out + grp * B, 0);
+  } else {
+    for (int64_t g0i = (int64_t)blockIdx.x * kThreads + threadIdx.x; g0i < nfull; g0i += stride) {
+      const int64_t grp = a.reverse ? nfull - 1 - g0i : g0i;
+      const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
+      const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
+      const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
+      const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+      unsigned __int128 v = 0;
+#pragma unroll
+      for (int j = 0; j < kGroup; ++j)
+        v |= (unsigned __int128)quant_one<B>(gv[j], hv[j], c, sh, accN, accS) << (j * B);
+      store_group<B>(out + grp * B, v);
+    }
+  }
+  // ragged tail (p % 8 coordinates) and zero fill up to the row stride
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int64_t byte = nfull * B;
+    if (a.p > nfull * kGroup) {
+      unsigned __int128 v = 0;
+      if (!c.zero)
+        for (int64_t i = nfull * kGroup; i < a.p; ++i)
+          v |= (unsigned __int128)quant_one<B>(g[i], h[i], c, sh, accN, accS)
+               << ((int)(i - nfull * kGroup) * B);
+      for (int k = 0; k < B; ++k) out[byte + k] = (uint8_t)(v >> (8 * k));
+      byte += B;
+    }
+    for (; byte < a.w_stride * 4; ++byte) out[byte] = 0;
+  }
+
+  // block totals of the two exact integer sums
+  unsigned long long s64 = wave_sum_u64(accS);
+  unsigned long long n64 = wave_sum_u64((unsigned long long)accN);
+  __shared__ unsigned long long smS[kThreads / 64], smN[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
+  __syncthreads();
+  __shared__ bool last_s;
+  if (threadIdx.x == 0) {
+    a.sc.Spart[(int64_t)m * a.slots + blockIdx.x] = smS[0] + smS[1] + smS[2] + smS[3];
+    a.sc.Npart[(int64_t)m * a.slots + blockIdx.x] = smN[0] + smN[1] + smN[2] + smN[3];
+    __threadfence();
+    last_s = (atomicAdd(&a.sc.ticket[m], 1u) == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!last_s) return;
+
+  // last block of worker m: totals of the block partials (integers: order-free)
+  __threadfence();
+  s64 = 0; n64 = 0;
+  for (int i = threadIdx.x; i < (int)gridDim.x; i += kThreads) {
+    s64 += __hip_atomic_load(&a.sc.Spart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    n64 += __hip_atomic_load(&a.sc.Npart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  s64 = wave_sum_u64(s64);
+  n64 = wave_sum_u64(n64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  const unsigned long long Sq = smS[0] + smS[1] + smS[2] + smS[3];
+  const unsigned long long N = smN[0] + smN[1] + smN[2] + smN[3];
+
+  // skip rule (eqs. 7a-7b), binary64, fixed order
+  const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
+  const double r = (double)c.R / (double)L;
+  const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
+  double Hsum = 0.0;
+  for (int d = 0; d < a.D; ++d) {
+    const double term = a.sc.xi[d] * a.sc.dtheta2[d];
+    Hsum = (d == 0) ? term : Hsum + term;
+  }
+  const double a2 = (double)a.alpha * (double)a.alpha;
+  const double m2 = (double)a.M * (double)a.M;
+  const double cc = 1.0 / (a2 * m2);
+  const double err = E2 + a.sc.Ehat2[m];
+  const double t1 = cc * Hsum;
+  const double t2 = 3.0 * err;
+  const double rhs = t1 + t2;
+  bool skip = (a.sc.t[m] < a.t_bar) && (lhs <= rhs);
+  if (a.mode & LAQ_MODE_FORCE_UPLOAD) skip = false;
+  if (!c.finite) { skip = true; atomicOr(a.sc.status, 1u); }
+  a.upload[m] = skip ? 0 : 1;
+  a.R_out[m] = c.R;
+  a.sc.Sq[m] = c.zero ? 0 : (long long)Sq;
+  a.sc.E2[m] = E2;
+  a.sc.lhs[m] = lhs;
+  a.sc.rhs[m] = rhs;
+  a.sc.ticket[m] = 0;
+}
+
+// ------------------------------------------------------------------ server step
+
+struct ServerArgs {
+  const uint32_t* codes;
+  const float* R_in;
+  const uint8_t* upload;
+  float* H;
+  float* nabla;
+  float* theta;
+  DeviceScalars sc;
+  int64_t p, p_stride, w_stride;
+  int32_t M, D, b;
+  float alpha;
+};
+
+// eq. 4: nabla^k = nabla^{k-1} + sum_{m in M^k} deltaQ_m, theta^{k+1} = theta^k - alpha nabla^k,
+// with Q_m(theta_hat_m) += deltaQ_m for the uploading workers (Alg. 2, upload branch).
+template <int B>
+__global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
+  constexpr uint32_t L = (1u << B) - 1u;
+  extern __shared__ unsigned char smem_raw[];
+  int32_t* list = reinterpret_cast<int32_t*>(smem_raw);           // [M] uploading workers, ascending
+  float* Rm = reinterpret_cast<float*>(list + a.M);               // [M]
+  float* stepm = Rm + a.M;                                        // [M]
+  __shared__ int n_up_s;
+
+  // ascending list of workers whose message carries a non-zero innovation
+  for (int m = threadIdx.x; m < a.M; m += kThreads) {
+    const float R = a.R_in[m];
+    const QuantConst c = quant_const<B>(__float_as_uint(R));
+    Rm[m] = R;
+    stepm[m] = (a.upload[m] && !c.zero) ? c.step : -1.0f;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int m = 0; m < a.M; ++m)
+      if (stepm[m] >= 0.0f) list[n++] = m;
+    n_up_s = n;
+  }
+  __syncthreads();
+  const int n_up = n_up_s;
+
+  const int64_t nfull = a.p / kGroup;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  double n2 = 0.0;
+  for (int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x; grp < nfull; grp += stride) {
+    float acc[kGroup];
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
+#pragma unroll 2
+    for (int k = 0; k < n_up; ++k) {
+      const int m = list[k];
+      const float R = Rm[m], step = stepm[m];
+      const unsigned __int128 v =
+          load_group<B>(reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride) + grp * B);
+      float4* hp = reinterpret_cast<float4*>(a.H + (int64_t)m * a.p_stride + grp * kGroup);
+      float4 h0 = hp[0], h1 = hp[1];
+      float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+#pragma unroll
+      for (int j = 0; j < kGroup; ++j) {
+        const uint32_t q = (uint32_t)(v >> (j * B)) & L;
+        float dq = (float)q * step;
+        dq = dq - R;
+        hv[j] = hv[j] + dq;
+        acc[j] = acc[j] + dq;
+      }
+      hp[0] = make_float4(hv[0], hv[1], hv[2], hv[3]);
+      hp[1] = make_float4(hv[4], hv[5], hv[6], hv[7]);
+    }
+    float4* np4 = reinterpret_cast<float4*>(a.nabla + grp * kGroup);
+    float4* tp4 = reinterpret_cast<float4*>(a.theta + grp * kGroup);
+    const float4 n0 = np4[0], n1 = np4[1], t0 = tp4[0], t1 = tp4[1];
+    float nv[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+    float tv[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) {
+      const float nb = nv[j] + acc[j];
+      nv[j] = nb;
+      const float st = a.alpha * nb;
+      tv[j] = tv[j] - st;
+      n2 = fma((double)nb, (double)nb, n2);
+    }
+    np4[0] = make_float4(nv[0], nv[1], nv[2], nv[3]);
+    np4[1] = make_float4(nv[4], nv[5], nv[6], nv[7]);
+    tp4[0] = make_float4(tv[0], tv[1], tv[2], tv[3]);
+    tp4[1] = make_float4(tv[4], tv[5], tv[6], tv[7]);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    for (int64_t i = nfull * kGroup; i < a.p; ++i) {
+      float acc = 0.0f;
+      for (int k = 0; k < n_up; ++k) {
+        const int m = list[k];
+        const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+        const int64_t bit = i * B;
+        uint32_t q = 0;
+        for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
+        float dq = (float)q * stepm[m];
+        dq = dq - Rm[m];
+        float* hp = a.H + (int64_t)m * a.p_stride + i;
+        *hp = *hp + dq;
+        acc = acc + dq;
+      }
+      const float nb = a.nabla[i] + acc;
+      a.nabla[i] = nb;
+      const float st = a.alpha * nb;
+      a.theta[i] = a.theta[i] - st;
+      n2 = fma((double)nb, (double)nb, n2);
+    }
+  }
+
+  n2 = wave_sum_f64(n2);
+  __shared__ double smd[kThreads / 64];
+  __shared__ bool last_s;
+  if ((threadIdx.x & 63) == 0) smd[threadIdx.x >> 6] = n2;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
+    __threadfence();
+    last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!last_s) return;
+  __threadfence();
+
+  // last block: bookkeeping of Algorithm 2 and the parameter-difference history
+  unsigned long long my_bits = 0;
+  for (int m = threadIdx.x; m < a.M; m += kThreads) {
+    if (a.upload[m]) {
+      a.sc.Ehat2[m] = a.sc.E2[m];
+      a.sc.t[m] = 0;
+      a.sc.uploads[m] += 1;
+      my_bits += 32ull + (unsigned long long)B * (unsigned long long)a.p;
+    } else {
+      a.sc.t[m] += 1;
+    }
+  }
+  if (my_bits) atomicAdd(a.sc.bits, my_bits);
+  if (threadIdx.x == 0) {
+    double tot = 0.0;
+    for (unsigned i = 0; i < gridDim.x; ++i)
+      tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int d = a.D - 1; d > 0; --d) a.sc.dtheta2[d] = a.sc.dtheta2[d - 1];
+    a.sc.dtheta2[0] = ((double)a.alpha * (double)a.alpha) * tot;
+    *a.sc.srv_ticket = 0;
+  }
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------ host side
+
+struct Layout {
+  size_t H, nabla, scalars, total;
+  size_t Rpart, Spart, Npart, ticket, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
+      dtheta2, xi, srv_part, scalars_end;
+};
+
+// Block-partial slots per worker in the two streaming passes.
+static int32_t partial_slots(int32_t M) {
+  if (M <= 64) return 2048;
+  const int32_t s = 131072 / M;
+  return s < 32 ? 32 : s;
+}
+
+static Layout make_layout(int32_t M, int64_t p, int32_t D) {
+  Layout l{};
+  const int64_t ps = laq_p_stride(p);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = (size_t)round_up((int64_t)(off + bytes), 256); return o; };
+  l.H = take((size_t)M * ps * sizeof(float));
+  l.nabla = take((size_t)ps * sizeof(float));
+  l.scalars = off;
+  const size_t slots = (size_t)partial_slots(M);
+  l.Rpart = take((size_t)M * slots * 4);
+  l.Spart = take((size_t)M * slots * 8);
+  l.Npart = take((size_t)M * slots * 8);
+  l.ticket = take((size_t)M * 4);
+  l.Sq = take((size_t)M * 8);
+  l.E2 = take((size_t)M * 8);
+  l.lhs = take((size_t)M * 8);
+  l.rhs = take((size_t)M * 8);
+  l.Ehat2 = take((size_t)M * 8);
+  l.t = take((size_t)M * 4);
+  l.uploads = take((size_t)M * 8);
+  l.bits = take(8);
+  l.status = take(4);
+  l.srv_ticket = take(4);
+  l.dtheta2 = take((size_t)D * 8);
+  l.xi = take((size_t)D * 8);
+  l.srv_part = take((size_t)kMaxServerBlocks * 8);
+  l.scalars_end = off;
+  l.total = off;
+  return l;
+}
+
+static bool valid_sizes(int32_t M, int64_t p, int32_t b, int32_t D) {
+  if (!(M >= 1 && M <= 65535 && p >= 1 && p < ((int64_t)1 << 31) && b >= 1 && b <= LAQ_MAX_BITS &&
+        D >= 1 && D <= 4096))
+    return false;
+  // every lane handles at most 512 groups of 8 coordinates per pass
+  return p / kGroup <= (int64_t)partial_slots(M) * kThreads * 512;
+}
+
+template <int B>
+static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a, int32_t m0) {
+  hipLaunchKernelGGL(codes_kernel<B>, grid, dim3(kThreads), 0, s, a, m0);
+}
+template <int B>
+static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArgs& a) {
+  hipLaunchKernelGGL(server_kernel<B>, grid, dim3(kThreads), smem, s, a);
+}
+
+#define LAQ_DISPATCH_B(b, CALL)                                                                   \
+  switch (b) {                                                                                    \
+    case 1: CALL(1); break;   case 2: CALL(2); break;   case 3: CALL(3); break;                    \
+    case 4: CALL(4); break;   case 5: CALL(5); break;   case 6: CALL(6); break;                    \
+    case 7: CALL(7); break;   case 8: CALL(8); break;   case 9: CALL(9); break;                    \
+    case 10: CALL(10); break; case 11: CALL(11); break; case 12: CALL(12); break;                  \
+    case 13: CALL(13); break; case 14: CALL(14); break; case 15: CALL(15); break;                  \
+    case 16: CALL(16); break;                                                                     \
+    default: break;                                                                               \
+  }
+
+// Blocks per worker for the streaming passes: enough blocks to fill the chip,
+// and at most 512 groups (4096 coordinates) per lane so that the per-lane
+// binary64 partial of the integer error sum stays below 2^53.
+static int blocks_per_worker(int64_t p, int32_t n_workers, int n_cu, int32_t slots) {
+  const int64_t nfull = p / kGroup;
+  int64_t by_work = (nfull + kThreads - 1) / kThreads;         // one group per lane
+  if (by_work < 1) by_work = 1;
+  int64_t want = ((int64_t)n_cu * 8 + n_workers - 1) / n_workers;   // ~8 blocks per CU in total
+  if (want < 1) want = 1;
+  int64_t bpw = by_work < want ? by_work : want;
+  const int64_t min_bpw = (nfull + (int64_t)kThreads * 512 - 1) / ((int64_t)kThreads * 512);
+  if (bpw < min_bpw) bpw = min_bpw;
+  if (bpw > slots) bpw = slots;
+  if (bpw < 1) bpw = 1;
+  return (int)bpw;
+}
+
+}  // namespace laq
+
+using namespace laq;
+
+extern "C" {
+
+int64_t laq_p_stride(int64_t p) { return round_up(p, 4); }
+
+int64_t laq_w_stride(int64_t p, int32_t b) {
+  const int64_t groups = (p + kGroup - 1) / kGroup;
+  const int64_t bytes = groups * b;
+  return round_up(bytes, 16) / 4;
+}
+
+size_t laq_workspace_bytes(int32_t M, int64_t p, int32_t b, int32_t D) {
+  if (!valid_sizes(M, p, b, D)) return 0;
+  return make_layout(M, p, D).total;
+}
+
+int laq_reset(laq_ctx* ctx) {
+  if (!ctx) return LAQ_EINVAL;
+  const Layout l = make_layout(ctx->M, ctx->p, ctx->D);
+  // H, nabla and every scalar except xi start at zero; clocks start at t_bar
+  LAQ_HIP(ctx, hipMemsetAsync(ctx->ws, 0, l.xi, ctx->stream));
+  LAQ_HIP(ctx, hipMemsetAsync(ctx->ws + l.srv_part, 0, l.total - l.srv_part, ctx->stream));
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((ctx->M + 255) / 256), dim3(256), 0, ctx->stream, ctx->sc.t,
+                     ctx->t_bar, ctx->M);
+  LAQ_HIP(ctx, hipGetLastError());
+  return LAQ_OK;
+}
+
+int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const float* xi,
+               int32_t t_bar, float alpha, void* workspace_dev, size_t workspace_bytes,
+               void* hip_stream) {
+  if (!out) return LAQ_EINVAL;
+  *out = nullptr;
+  if (!valid_sizes(M, p, b, D) || !xi || !workspace_dev) return LAQ_EINVAL;
+  if (t_bar < D || !(alpha > 0.0f) || !isfinite(alpha)) return LAQ_EINVAL;
+  for (int d = 0; d < D; ++d)
+    if (!(xi[d] >= 0.0f) || !isfinite(xi[d])) return LAQ_EINVAL;
+  if (((uintptr_t)workspace_dev & 255) != 0) return LAQ_EINVAL;
+  const Layout l = make_layout(M, p, D);
+  if (workspace_bytes < l.total) return LAQ_EINVAL;
+
+  laq_ctx* ctx = new (std::nothrow) laq_ctx();
+  if (!ctx) return LAQ_EINVAL;
+  ctx->M = M; ctx->p = p; ctx->b = b; ctx->D = D; ctx->t_bar = t_bar; ctx->alpha = alpha;
+  ctx->p_stride = laq_p_stride(p);
+  ctx->w_stride = laq_w_stride(p, b);
+  int K = (63 - ceil_log2(p)) / 2;
+  ctx->eps_K = K < 20 ? K : 20;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->ws = (uint8_t*)workspace_dev;
+  ctx->ws_bytes = workspace_bytes;
+  uint8_t* w = ctx->ws;
+  ctx->H = (float*)(w + l.H);
+  ctx->nabla = (float*)(w + l.nabla);
+  DeviceScalars& s = ctx->sc;
+  s.Rpart = (uint32_t*)(w + l.Rpart);
+  s.Spart = (unsigned long long*)(w + l.Spart);
+  s.Npart = (unsigned long long*)(w + l.Npart);
+  s.ticket = (uint32_t*)(w + l.ticket);
+  s.Sq = (long long*)(w + l.Sq);
+  s.E2 = (double*)(w + l.E2);
+  s.lhs = (double*)(w + l.lhs);
+  s.rhs = (double*)(w + l.rhs);
+  s.Ehat2 = (double*)(w + l.Ehat2);
+  s.t = (int32_t*)(w + l.t);
+  s.uploads = (unsigned long long*)(w + l.uploads);
+  s.bits = (unsigned long long*)(w + l.bits);
+  s.status = (uint32_t*)(w + l.status);
+  s.srv_ticket = (uint32_t*)(w + l.srv_ticket);
+  s.dtheta2 = (double*)(w + l.dtheta2);
+  s.xi = (double*)(w + l.xi);
+  s.srv_part = (double*)(w + l.srv_part);
+
+  auto fail = [&](int st) { delete ctx; return st; };
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e != hipSuccess) return fail(LAQ_EDEVICE);
+  int n_cu = 0;
+  e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
+  if (e != hipSuccess || n_cu <= 0) return fail(LAQ_EDEVICE);
+  ctx->n_cu = n_cu;
+
+  // workers per quantize launch pair: keep one pair's operands (g and h rows)
+  // within a budget that the memory-side cache can hold between the two passes
+  long long budget_mb = 96;
+  if (const char* env = getenv("LAQ_GROUP_MB")) { long long v = atoll(env); if (v > 0) budget_mb = v; }
+  int64_t per_worker = ctx->p_stride * 8;
+  int64_t gw = (budget_mb << 20) / (per_worker > 0 ? per_worker : 1);
+  if (gw < 1) gw = 1;
+  if (gw > M) gw = M;
+  ctx->group_workers = gw;
+  ctx->reverse_pass2 = 1;
+  if (const char* env = getenv("LAQ_REVERSE")) ctx->reverse_pass2 = atoi(env) ? 1 : 0;
+
+  double xi64[4096];
+  for (int d = 0; d < D; ++d) xi64[d] = (double)xi[d];
+  int st = laq_reset(ctx);
+  if (st != LAQ_OK) return fail(st);
+  e = hipMemcpyAsync(s.xi, xi64, (size_t)D * 8, hipMemcpyHostToDevice, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return fail(LAQ_EDEVICE);
+  *out = ctx;
+  return LAQ_OK;
+}
+
+int laq_destroy(laq_ctx* ctx) {
+  if (!ctx) return LAQ_EINVAL;
+  delete ctx;
+  return LAQ_OK;
+}
+
+int laq_set_mode(laq_ctx* ctx, uint32_t flags) {
+  if (!ctx || (flags & ~LAQ_MODE_FORCE_UPLOAD)) return LAQ_EINVAL;
+  ctx->mode = flags;
+  return LAQ_OK;
+}
+
+int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, float* R_dev,
+                      uint8_t* upload_dev) {
+  if (!ctx) return LAQ_EINVAL;
+  if (!G_dev || !codes_dev || !R_dev || !upload_dev)
+    return set_error(ctx, LAQ_EINVAL, "laq_quantize_skip: null pointer");
+  if (((uintptr_t)G_dev | (uintptr_t)codes_dev) & 15)
+    return set_error(ctx, LAQ_EINVAL, "laq_quantize_skip: G_dev and codes_dev must be 16-byte aligned");
+  QuantArgs a{};
+  a.G = G_dev; a.H = ctx->H; a.codes = codes_dev; a.R_out = R_dev; a.upload = upload_dev;
+  a.sc = ctx->sc;
+  a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
+  a.M = ctx->M; a.D = ctx->D; a.t_bar = ctx->t_bar; a.eps_K = ctx->eps_K;
+  a.slots = partial_slots(ctx->M);
+  a.reverse = ctx->reverse_pass2;
+  a.alpha = ctx->alpha; a.mode = ctx->mode;
+  for (int32_t m0 = 0; m0 < ctx->M; m0 += (int32_t)ctx->group_workers) {
+    const int32_t nw = (int32_t)((ctx->M - m0) < ctx->group_workers ? (ctx->M - m0) : ctx->group_workers);
+    const int bpw = blocks_per_worker(ctx->p, nw, ctx->n_cu, a.slots);
+    const dim3 grid((unsigned)bpw, (unsigned)nw);
+    hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
+                       ctx->p_stride, m0, a.slots, ctx->sc.Rpart);
+#define LAQ_CALL(BB) launch_codes<BB>(grid, ctx->stream, a, m0)
+    LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
+#undef LAQ_CALL
+  }
+  LAQ_HIP(ctx, hipGetLastError());
+  return LAQ_OK;
+}
+
+int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
+                    const uint8_t* upload_dev, float* theta_dev) {
+  if (!ctx) return LAQ_EINVAL;
+  if (!codes_dev || !R_dev || !upload_dev || !theta_dev)
+    return set_error(ctx, LAQ_EINVAL, "laq_server_step: null pointer");
+  if (((uintptr_t)codes_dev | (uintptr_t)theta_dev) & 15)
+    return set_error(ctx, LAQ_EINVAL, "laq_server_step: codes_dev and theta_dev must be 16-byte aligned");
+  ServerArgs a{};
+  a.codes = codes_dev; a.R_in = R_dev; a.upload = upload_dev;
+  a.H = ctx->H; a.nabla = ctx->nabla; a.theta = theta_dev; a.sc = ctx->sc;
+  a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
+  a.M = ctx->M; a.D = ctx->D; a.b = ctx->b; a.alpha = ctx->alpha;
+  const int64_t nfull = ctx->p / kGroup;
+  int64_t blocks = (nfull + kThreads - 1) / kThreads;
+  const int64_t cap = (int64_t)ctx->n_cu * 8 < kMaxServerBlocks ? (int64_t)ctx->n_cu * 8 : kMaxServerBlocks;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  const size_t smem = (size_t)ctx->M * 12;
+  const dim3 grid((unsigned)blocks);
+#define LAQ_CALL(BB) launch_server<BB>(grid, smem, ctx->stream, a)
+  LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
+#undef LAQ_CALL
+  LAQ_HIP(ctx, hipGetLastError());
+  return LAQ_OK;
+}
+
+int laq_get_state(laq_ctx* ctx, laq_state_view* v) {
+  if (!ctx || !v) return LAQ_EINVAL;
+  v->H_dev = ctx->H;
+  v->nabla_dev = ctx->nabla;
+  v->Ehat2_dev = ctx->sc.Ehat2;
+  v->t_dev = ctx->sc.t;
+  v->dtheta2_dev = ctx->sc.dtheta2;
+  v->Sq_dev = (int64_t*)ctx->sc.Sq;
+  v->E2_dev = ctx->sc.E2;
+  v->lhs_dev = ctx->sc.lhs;
+  v->rhs_dev = ctx->sc.rhs;
+  v->uploads_dev = (uint64_t*)ctx->sc.uploads;
+  v->bits_dev = (uint64_t*)ctx->sc.bits;
+  v->status_dev = ctx->sc.status;
+  v->p_stride = ctx->p_stride;
+  v->w_stride = ctx->w_stride;
+  return LAQ_OK;
+}
+
+int laq_get_counters(laq_ctx* ctx, uint64_t* uploads, uint64_t* bits_total) {
+  if (!ctx) return LAQ_EINVAL;
+  uint32_t status = 0;
+  if (uploads)
+    LAQ_HIP(ctx, hipMemcpyAsync(uploads, ctx->sc.uploads, (size_t)ctx->M * 8, hipMemcpyDeviceToHost, ctx->stream));
+  if (bits_total)
+    LAQ_HIP(ctx, hipMemcpyAsync(bits_total, ctx->sc.bits, 8, hipMemcpyDeviceToHost, ctx->stream));
+  LAQ_HIP(ctx, hipMemcpyAsync(&status, ctx->sc.status, 4, hipMemcpyDeviceToHost, ctx->stream));
+  LAQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (status) return set_error(ctx, LAQ_ENONFINITE, "a quantization radius was not finite");
+  return LAQ_OK;
+}
+
+const char* laq_last_error(const laq_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int laq_set_model(laq_ctx* ctx, int32_t kind, const int32_t* dims, int32_t n_dims, float lambda) {
+  if (!ctx) return LAQ_EINVAL;
+  if (!(lambda >= 0.0f) || !isfinite(lambda)) return set_error(ctx, LAQ_EINVAL, "lambda must be >= 0");
+  if (kind == LAQ_MODEL_NONE) { ctx->kind = kind; return LAQ_OK; }
+  if (!dims) return set_error(ctx, LAQ_EINVAL, "dims is null");
+  int64_t pp = 0;
+  if (kind == LAQ_MODEL_BINLOG) {
+    if (n_dims != 1 || dims[0] < 1) return set_error(ctx, LAQ_EINVAL, "binary logistic: dims = {F}");
+    pp = dims[0]; ctx->F = dims[0]; ctx->C = 1;
+  } else if (kind == LAQ_MODEL_SOFTMAX) {
+    if (n_dims != 2 || dims[0] < 1 || dims[1] < 2) return set_error(ctx, LAQ_EINVAL, "softmax: dims = {F, C}");
+    pp = (int64_t)dims[0] * dims[1]; ctx->F = dims[0]; ctx->C = dims[1];
+  } else if (kind == LAQ_MODEL_MLP) {
+    if (n_dims < 2 || n_dims > LAQ_MAX_LAYERS + 1) return set_error(ctx, LAQ_EINVAL, "mlp: 2..%d widths", LAQ_MAX_LAYERS + 1);
+    Mlp& n = ctx->mlp;
+    n.n_layers = n_dims - 1;
+    int64_t off = 0;
+    for (int l = 0; l < n_dims; ++l) {
+      if (dims[l] < 1) return set_error(ctx, LAQ_EINVAL, "mlp: widths must be >= 1");
+      n.dims[l] = dims[l];
+    }
+    for (int l = 0; l < n.n_layers; ++l) {
+      n.offW[l] = off; off += (int64_t)dims[l] * dims[l + 1];
+      n.offB[l] = off; off += dims[l + 1];
+    }
+    pp = off; ctx->F = dims[0]; ctx->C = dims[n_dims - 1];
+  } else {
+    return set_error(ctx, LAQ_EINVAL, "unknown model kind %d", kind);
+  }
+  if (pp != ctx->p) return set_error(ctx, LAQ_EINVAL, "model has %lld parameters, context has p = %lld", (long long)pp, (long long)ctx->p);
+  ctx->kind = kind;
+  ctx->lambda = lambda;
+  ctx->X = nullptr; ctx->y = nullptr; ctx->model_ws = nullptr;
+  return LAQ_OK;
+}
+
+size_t laq_model_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
+  if (!ctx || N_m < 1) return 0;
+  return model_workspace_bytes(ctx, N_m);
+}
+
+int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t N_m, int64_t ldx,
+                 void* model_ws_dev, size_t model_ws_bytes) {
+  if (!ctx) return LAQ_EINVAL;
+  if (ctx->kind == LAQ_MODEL_NONE) return set_error(ctx, LAQ_ESTATE, "laq_set_data before laq_set_model");
+  if (!X_dev || !y_dev || N_m < 1 || ldx < ctx->F || (ldx & 3) || ((uintptr_t)X_dev & 15))
+    return set_error(ctx, LAQ_EINVAL, "laq_set_data: bad X/y/N_m/ldx");
+  const size_t need = model_workspace_bytes(ctx, N_m);
+  if (need && (!model_ws_dev || model_ws_bytes < need || ((uintptr_t)model_ws_dev & 255)))
+    return set_error(ctx, LAQ_EINVAL, "laq_set_data: model workspace too small or misaligned (need %zu bytes)", need);
+  ctx->X = X_dev; ctx->y = y_dev; ctx->N_m = N_m; ctx->ldx = ldx;
+  ctx->model_ws = (uint8_t*)model_ws_dev; ctx->model_ws_bytes = model_ws_bytes;
+  return LAQ_OK;
+}
+
+int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev) {
+  if (!ctx) return LAQ_EINVAL;
+  if (ctx->kind == LAQ_MODEL_NONE || !ctx->X)
+    return set_error(ctx, LAQ_ESTATE, "laq_worker_grads needs laq_set_model and laq_set_data");
+  if (!theta_dev || !G_dev || (((uintptr_t)theta_dev | (uintptr_t)G_dev) & 15))
+    return set_error(ctx, LAQ_EINVAL, "laq_worker_grads: null or misaligned pointer");
+  return worker_grads(ctx, theta_dev, G_dev);
+}
+
+}  // extern "C"

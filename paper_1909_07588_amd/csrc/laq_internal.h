@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of liblaq_hip.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "laq.h"
+
+namespace laq {
+
+constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes
+constexpr int kGroup = 8;              // elements owned by one lane per step: 8*b bits = b whole bytes
+constexpr int kMaxServerBlocks = 4096; // partial sums of ||nabla||^2
+
+// Per-worker and global scalars kept in the device workspace.
+struct DeviceScalars {
+  uint32_t* Rpart;              // [M][slots] block maxima of |g-h| (raw bits)
+  unsigned long long* Spart;    // [M][slots] block sums of (2q-L)^2
+  unsigned long long* Npart;    // [M][slots] block sums of the integer error squares
+  uint32_t* ticket;             // [M] blocks finished for worker m (reset after use)
+  long long* Sq;                // [M] stash
+  double* E2;                   // [M] stash
+  double* lhs;                  // [M]
+  double* rhs;                  // [M]
+  double* Ehat2;                // [M]
+  int32_t* t;                   // [M]
+  unsigned long long* uploads;  // [M]
+  unsigned long long* bits;     // [1]
+  uint32_t* status;             // [1]
+  uint32_t* srv_ticket;         // [1]
+  double* dtheta2;              // [D]
+  double* xi;                   // [D]
+  double* srv_part;             // [kMaxServerBlocks]
+};
+
+struct Mlp {
+  int32_t n_layers = 0;                 // weight layers
+  int32_t dims[LAQ_MAX_LAYERS + 1] = {0};
+  int64_t offW[LAQ_MAX_LAYERS] = {0};
+  int64_t offB[LAQ_MAX_LAYERS] = {0};
+};
+
+}  // namespace laq
+
+struct laq_ctx {
+  int32_t M = 0;
+  int64_t p = 0, p_stride = 0, w_stride = 0;
+  int32_t b = 0, D = 0, t_bar = 0, eps_K = 0;
+  float alpha = 0.f;
+  uint32_t mode = 0;
+  hipStream_t stream = nullptr;
+  int device = 0;
+  int n_cu = 256;
+
+  uint8_t* ws = nullptr;
+  size_t ws_bytes = 0;
+  float* H = nullptr;
+  float* nabla = nullptr;
+  laq::DeviceScalars sc{};
+  size_t scalars_offset = 0, scalars_bytes = 0;
+  int64_t group_workers = 0;     // workers per quantize launch pair (cache residency)
+  int32_t reverse_pass2 = 1;     // second pass walks the data backwards
+
+  // model
+  int32_t kind = LAQ_MODEL_NONE;
+  float lambda = 0.f;
+  int32_t F = 0, C = 0;
+  laq::Mlp mlp{};
+  const float* X = nullptr;
+  const int32_t* y = nullptr;
+  int64_t N_m = 0, ldx = 0;
+  uint8_t* model_ws = nullptr;
+  size_t model_ws_bytes = 0;
+
+  char err[512] = {0};
+};
+
+namespace laq {
+
+int set_error(laq_ctx* ctx, int status, const char* fmt, ...);
+
+#define LAQ_HIP(ctx, expr)                                                          \
+  do {                                                                              \
+    hipError_t _e = (expr);                                                         \
+    if (_e != hipSuccess)                                                           \
+      return laq::set_error((ctx), LAQ_EDEVICE, "%s failed: %s (%s:%d)", #expr,     \
+                            hipGetErrorString(_e), __FILE__, __LINE__);             \
+  } while (0)
+
+// gradient kernels (laq_grads.hip)
+size_t model_workspace_bytes(const laq_ctx* ctx, int64_t N_m);
+int worker_grads(laq_ctx* ctx, const float* theta, float* G);
+
+}  // namespace laq

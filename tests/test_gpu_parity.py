@@ -1,0 +1,247 @@
+"""Parity of the HIP path (through the C ABI binding) with the CPU oracle.
+
+Bar: radii, codes, upload masks, the two integer sums, both sides of (7a),
+stored quantized gradients, nabla and theta bit-exact when both sides are fed
+the same gradients and state; the binary64 history entry alpha^2||nabla||^2
+within 4 p 2^-53 relative (its summation order is free); model gradients within 1e-5 of
+the largest gradient entry.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import laq_synth
+import oracle
+from gpu_common import (DEV, bits_equal, check_quantize, check_server, make_pair, push_state,
+                        to_dev_G)
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_state(st, rng, scale=1.0):
+    """A mid-run state: stored gradients, clocks, error norms, history."""
+    M, p = st.M, st.p
+    st.H[:] = (rng.standard_normal((M, p)) * scale).astype(np.float32)
+    st.nabla[:] = st.H.sum(0)
+    st.theta[:] = rng.standard_normal(p).astype(np.float32)
+    st.Ehat2[:] = rng.random(M) * 1e-3 * scale ** 2
+    st.t[:] = rng.integers(0, st.t_bar + 1, M)
+    st.dtheta2[:] = rng.random(st.D) * 1e-4 * scale ** 2
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 7, 8, 11, 16])
+@pytest.mark.parametrize("M,p", [(1, 1), (2, 7), (3, 8), (2, 9), (10, 50), (4, 2049), (10, 7850)])
+def test_one_iteration_from_a_random_state(b, M, p):
+    rng = np.random.default_rng(1000 * b + p)
+    ctx, st, theta = make_pair(M, p, b, D=4, t_bar=6, alpha=0.05)
+    _random_state(st, rng)
+    push_state(ctx, st)
+    theta.copy_(torch.from_numpy(st.theta))
+    # innovations of very different sizes: some workers skip, some upload
+    G = (st.H + rng.standard_normal((M, p)).astype(np.float32)
+         * (10.0 ** rng.uniform(-4, 0, (M, 1))).astype(np.float32)).astype(np.float32)
+    Gd = to_dev_G(ctx, G)
+    msgs, _ = check_quantize(ctx, st, Gd, G)
+    # repeated call: same answer (the call leaves the state untouched)
+    msgs2, _ = check_quantize(ctx, st, Gd, G)
+    check_server(ctx, st, theta, msgs, G)
+
+
+@pytest.mark.parametrize("b,p", [(2, 300_007), (4, (1 << 20) + 5), (8, 1_000_003), (3, 524_288)])
+def test_many_tiles_and_ragged_tail(b, p):
+    rng = np.random.default_rng(b * 7 + p)
+    M = 5
+    ctx, st, theta = make_pair(M, p, b, D=10, t_bar=50, alpha=0.01)
+    scales = laq_synth.worker_scales(M)
+    G = laq_synth.host_gradients(M, p, scales=scales)
+    Gd = to_dev_G(ctx, G)
+    for it in range(3):
+        msgs, _ = check_quantize(ctx, st, Gd, G)
+        check_server(ctx, st, theta, msgs, G)
+        push_state(ctx, st)            # impose the oracle's history entry (its order-free part)
+        G = laq_synth.host_drift(G, it, scales=scales)
+        Gd[:, :p].copy_(torch.from_numpy(G))
+
+
+def test_teacher_forced_run_skips_and_uploads():
+    """30 iterations of drifting synthetic gradients: every mask, code and iterate equal."""
+    M, p, b = 12, 40_000, 4
+    ctx, st, theta = make_pair(M, p, b, D=5, t_bar=8, alpha=0.01)
+    scales = laq_synth.worker_scales(M)
+    G = laq_synth.host_gradients(M, p, scales=scales)
+    Gd = to_dev_G(ctx, G)
+    n_up = 0
+    for it in range(30):
+        msgs, _ = check_quantize(ctx, st, Gd, G)
+        out = check_server(ctx, st, theta, msgs, G)
+        n_up += int(out["upload"].sum())
+        push_state(ctx, st)
+        G = laq_synth.host_drift(G, it, scales=scales)
+        Gd[:, :p].copy_(torch.from_numpy(G))
+    assert M < n_up < 30 * M            # the run exercised both branches
+    up, bits, status = ctx.laq_get_counters()
+    assert status == 0 and int(up.sum()) == n_up and bits == n_up * (32 + b * p)
+
+
+def test_free_running_run_stays_on_the_oracle_trajectory():
+    """No state is copied: iterates within 1e-5 per iteration; masks reported."""
+    M, p, b = 8, 20_000, 8
+    ctx, st, theta = make_pair(M, p, b, D=5, t_bar=8, alpha=0.01)
+    scales = laq_synth.worker_scales(M)
+    G = laq_synth.host_gradients(M, p, scales=scales)
+    Gd = to_dev_G(ctx, G)
+    msgs = ctx.alloc_messages()
+    agree = 0
+    for it in range(25):
+        ctx.laq_quantize_skip(Gd, *msgs)
+        ctx.laq_server_step(*msgs, theta)
+        out = st.iteration(G)
+        th = theta.cpu().numpy()
+        assert np.abs(th - st.theta).max() <= 1e-5 * np.abs(st.theta).max(), it
+        agree += int(np.array_equal(msgs[2].cpu().numpy(), out["upload"]))
+        G = laq_synth.host_drift(G, it, scales=scales)
+        Gd[:, :p].copy_(torch.from_numpy(G))
+    assert agree == 25
+
+
+def test_zero_innovation_and_forced_upload_clock():
+    M, p, b = 4, 1000, 4
+    rng = np.random.default_rng(3)
+    ctx, st, theta = make_pair(M, p, b, D=2, t_bar=3, alpha=0.1)
+    _random_state(st, rng)
+    st.t[:] = [0, 3, 1, 3]                      # workers 1 and 3 have reached t_bar
+    push_state(ctx, st)
+    theta.copy_(torch.from_numpy(st.theta))
+    G = st.H.copy()                             # zero innovation everywhere
+    G[2] += rng.standard_normal(p).astype(np.float32)
+    Gd = to_dev_G(ctx, G)
+    msgs, ref = check_quantize(ctx, st, Gd, G)
+    up = msgs[2].cpu().numpy()
+    assert list(up) == [0, 1, 1, 1]
+    assert msgs[1].cpu().numpy()[0] == 0.0 and not msgs[0][0].any()
+    check_server(ctx, st, theta, msgs, G)
+
+
+def test_force_upload_mode_is_algorithm_1():
+    M, p, b = 6, 3001, 3
+    rng = np.random.default_rng(4)
+    ctx, st, theta = make_pair(M, p, b, D=3, t_bar=9, alpha=0.02)
+    ctx.laq_set_mode(1)
+    G = rng.standard_normal((M, p)).astype(np.float32)
+    Gd = to_dev_G(ctx, G)
+    for it in range(4):
+        msgs, _ = check_quantize(ctx, st, Gd, G, force=True)
+        assert msgs[2].cpu().numpy().all()
+        check_server(ctx, st, theta, msgs, G, force=True)
+        push_state(ctx, st)
+        G = (G + 1e-3 * rng.standard_normal((M, p))).astype(np.float32)
+        Gd[:, :p].copy_(torch.from_numpy(G))
+
+
+def test_nonfinite_radius_sets_the_status_word():
+    M, p, b = 3, 100, 4
+    ctx, st, theta = make_pair(M, p, b)
+    G = np.ones((M, p), np.float32)
+    G[1, 17] = np.inf
+    Gd = to_dev_G(ctx, G)
+    msgs = ctx.alloc_messages()
+    ctx.laq_quantize_skip(Gd, *msgs)
+    _, _, status = ctx.laq_get_counters()
+    assert status == 4
+    assert msgs[2].cpu().numpy()[1] == 0         # the faulty worker is not aggregated
+
+
+def test_worker_groups_smaller_than_M(monkeypatch):
+    """Workers are quantized in several launch pairs when their rows exceed the cache budget."""
+    monkeypatch.setenv("LAQ_GROUP_MB", "1")
+    M, p, b = 7, 60_000, 4                      # 480 KB per worker -> 2 workers per pair
+    rng = np.random.default_rng(9)
+    ctx, st, theta = make_pair(M, p, b, D=5, t_bar=10)
+    G = rng.standard_normal((M, p)).astype(np.float32)
+    Gd = to_dev_G(ctx, G)
+    msgs, _ = check_quantize(ctx, st, Gd, G)
+    check_server(ctx, st, theta, msgs, G)
+
+
+def test_bad_arguments_are_rejected():
+    import ctypes as C
+    import paper_1909_07588_amd as laq
+    L = laq.lib()
+    h = C.c_void_p()
+    xi = (C.c_float * 2)(0.1, 0.1)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    args = lambda **k: [C.byref(h), k.get("M", 2), k.get("p", 100), k.get("b", 4), k.get("D", 2), xi,
+                        k.get("t_bar", 5), C.c_float(k.get("alpha", 0.1)),
+                        C.c_void_p(ws.data_ptr() + k.get("mis", 0)), k.get("bytes", 1 << 20), None]
+    assert L.laq_create(*args(b=0)) == 1
+    assert L.laq_create(*args(b=17)) == 1
+    assert L.laq_create(*args(M=0)) == 1
+    assert L.laq_create(*args(D=6)) == 1        # D <= t_bar
+    assert L.laq_create(*args(alpha=0.0)) == 1
+    assert L.laq_create(*args(bytes=16)) == 1
+    assert L.laq_create(*args(mis=4)) == 1
+    assert L.laq_create(*args()) == 0
+    assert L.laq_worker_grads(h, None, None) == 2      # no model bound
+    assert L.laq_quantize_skip(h, None, None, None, None) == 1
+    assert L.laq_destroy(h) == 0
+
+
+# --------------------------------------------------------------------------- model gradients
+
+def _grad_case(w):
+    X, y, theta0 = laq_synth.model_inputs(w)
+    rng = np.random.default_rng(w.cfg)
+    theta = (theta0 + 0.05 * rng.standard_normal(w.p)).astype(np.float32)
+    ctx, st, _ = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    th_d = torch.from_numpy(theta).to(DEV)
+    Gd = ctx.alloc_G()
+    ctx.laq_worker_grads(th_d, Gd)
+    torch.cuda.synchronize()
+    G_ref, _ = oracle.grads_all(w.kind, theta, X, y, w.dims, w.lam)
+    return Gd[:, :w.p].cpu().numpy(), G_ref
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, 1.0), (2, 0.05), (2, 0.011)])
+def test_logistic_gradients_match_the_oracle(cfg, scale):
+    w = laq_synth.workload(cfg, scale)
+    G, G_ref = _grad_case(w)
+    err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
+    assert err.max() <= 1e-5, err
+
+
+@pytest.mark.parametrize("F,C,N_m,M", [(3, 2, 5, 2), (64, 4, 33, 3), (65, 10, 100, 2), (513, 16, 47, 2),
+                                       (1000, 7, 19, 1)])
+def test_softmax_gradient_shapes(F, C, N_m, M):
+    w = laq_synth.Workload("t", 2, laq_synth.KIND_SOFTMAX, M, N_m, (F, C), F * C, 4)
+    G, G_ref = _grad_case(w)
+    err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
+    assert err.max() <= 1e-5, err
+
+
+def test_full_loop_on_the_smallest_workload():
+    """Config 1, all four steps on the GPU, teacher-forced: the oracle quantizes
+    the GPU's gradients (compared to its own within 1e-5) from the same state."""
+    w = laq_synth.workload(1)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    ctx, st, theta = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta0)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    Gd = ctx.alloc_G()
+    msgs = ctx.alloc_messages()
+    skipped = 0
+    for it in range(w.iterations):
+        ctx.laq_worker_grads(theta, Gd)
+        torch.cuda.synchronize()
+        G = Gd[:, :w.p].cpu().numpy()
+        G_ref, _ = oracle.grads_all(w.kind, st.theta, X, y, w.dims, w.lam)
+        err = np.abs(G - G_ref).max() / np.abs(G_ref).max()
+        assert err <= 1e-5, (it, err)
+        msgs, _ = check_quantize(ctx, st, Gd, G, msgs)
+        out = check_server(ctx, st, theta, msgs, G)
+        skipped += int((out["upload"] == 0).sum())
+        push_state(ctx, st)
+    assert skipped > w.iterations          # lazy aggregation is active on this problem

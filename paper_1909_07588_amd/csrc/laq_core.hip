@@ -88,41 +88,77 @@ __device__ __forceinline__ QuantConst quant_const(uint32_t rbits) {
   return c;
 }
 
+// ------------------------------------------------------------------ sweep geometry
+//
+// Both streaming passes use a grid of (ceil(T/U), M) blocks: block (x, m)
+// handles U consecutive tiles of 256 groups (2048 coordinates each) of worker
+// m, U = 1 unless p is very large.  The hardware dispatches blocks in order
+// (x fastest), so at any moment the resident blocks work on one contiguous
+// window of one or two workers' rows: few concurrent DRAM streams, which is
+// worth ~15 % of bandwidth on this part compared with a grid that keeps all
+// workers' rows in flight.  Every block leaves its partial results in its own
+// slot and a small follow-up kernel combines them: no atomics or device-scope
+// fences inside the sweeps (a release fence writes back the whole L2 here and
+// costs microseconds; thousands of same-address atomics serialise).
+
+constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kMaxSlots = 8192;   // block partials per worker
+
+struct Sweep {
+  int64_t nfull;   // whole groups of 8 coordinates per worker
+  int64_t T;       // tiles of 256 groups per worker (>= 1)
+  int32_t U;       // consecutive tiles per block
+  int32_t Gx;      // blocks per worker
+};
+
 // ------------------------------------------------------------------ pass 1: radius
 
 // R_m = || g_m - h_m ||_inf (Sec. 2.1).  The maximum is taken on the raw
-// bits of |d| (order-free, exact, NaN > inf so a NaN is not lost).  Each block
-// leaves its partial maximum in Rpart[m][block]; the second pass combines them
-// (no same-address atomics: thousands of them serialise at the memory side).
+// bits of |d| (order-free, exact, NaN > inf so a NaN is not lost).
 __global__ __launch_bounds__(kThreads) void radius_kernel(const float* __restrict__ G,
                                                           const float* __restrict__ H, int64_t p,
-                                                          int64_t p_stride, int32_t m0, int32_t slots,
-                                                          uint32_t* __restrict__ Rpart) {
-  const int m = m0 + blockIdx.y;
-  const float* g = G + (int64_t)m * p_stride;
-  const float* h = H + (int64_t)m * p_stride;
+                                                          int64_t p_stride, int32_t U, int32_t slots,
+                                                          DeviceScalars sc) {
   const int64_t nfull = p / kGroup;
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
-  uint32_t mx = 0;
-  for (int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x; grp < nfull; grp += stride) {
-    const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
-    const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
-    const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
-    uint32_t a = max(max(abs_bits(g0.x - h0.x), abs_bits(g0.y - h0.y)),
-                     max(abs_bits(g0.z - h0.z), abs_bits(g0.w - h0.w)));
-    uint32_t c = max(max(abs_bits(g1.x - h1.x), abs_bits(g1.y - h1.y)),
-                     max(abs_bits(g1.z - h1.z), abs_bits(g1.w - h1.w)));
-    mx = max(mx, max(a, c));
+  {
+    const int m = blockIdx.y;
+    const float* g = G + (int64_t)m * p_stride;
+    const float* h = H + (int64_t)m * p_stride;
+    uint32_t mx = 0;
+    const int64_t first = (int64_t)blockIdx.x * U * kThreads + threadIdx.x;
+    for (int64_t grp = first, u = 0; u < U && grp < nfull; ++u, grp += kThreads) {
+      const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
+      const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
+      const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
+      uint32_t a = max(max(abs_bits(g0.x - h0.x), abs_bits(g0.y - h0.y)),
+                       max(abs_bits(g0.z - h0.z), abs_bits(g0.w - h0.w)));
+      uint32_t c = max(max(abs_bits(g1.x - h1.x), abs_bits(g1.y - h1.y)),
+                       max(abs_bits(g1.z - h1.z), abs_bits(g1.w - h1.w)));
+      mx = max(mx, max(a, c));
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+      for (int64_t i = nfull * kGroup; i < p; ++i) mx = max(mx, abs_bits(g[i] - h[i]));
+    // one partial per block (the barrier comes after the block's last load)
+    __shared__ uint32_t sm[kWavesPerBlock];
+    mx = wave_max_u32(mx);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      sc.Rpart[(int64_t)m * slots + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0)
-    for (int64_t i = nfull * kGroup; i < p; ++i) mx = max(mx, abs_bits(g[i] - h[i]));
+}
 
-  mx = wave_max_u32(mx);
+// R_m from the block partials of the first pass.
+__global__ __launch_bounds__(kThreads) void radius_final_kernel(int32_t n_slots, int32_t slots,
+                                                                DeviceScalars sc) {
   __shared__ uint32_t sm[kThreads / 64];
+  const int m = blockIdx.x;
+  uint32_t mx = 0;
+  for (int i = threadIdx.x; i < n_slots; i += kThreads) mx = max(mx, sc.Rpart[(int64_t)m * slots + i]);
+  mx = wave_max_u32(mx);
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
   __syncthreads();
-  if (threadIdx.x == 0)
-    Rpart[(int64_t)m * slots + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
+  if (threadIdx.x == 0) sc.Rfin[m] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
 // ------------------------------------------------------------------ pass 2: codes + skip rule
@@ -135,7 +171,7 @@ struct QuantArgs {
   uint8_t* upload;
   DeviceScalars sc;
   int64_t p, p_stride, w_stride;
-  int32_t M, D, t_bar, eps_K, slots, reverse;
+  int32_t M, D, t_bar, eps_K, slots, fused_radius, U;
   float alpha;
   uint32_t mode;
 };
@@ -158,8 +194,8 @@ __device__ __forceinline__ uint32_t quant_one(float g, float h, const QuantConst
   const float e = g - hn;
   const double nd = (double)rintf(ldexpf(e, sh));   // integer-valued, |nd| < 2^21
   accN = fma(nd, nd, accN);                          // exact while accN < 2^53
-  const int cc = 2 * (int)qi - L;
-  accS += (unsigned long long)(uint32_t)(cc * cc);
+  const int cc = 2 * (int)qi - L;                    // |cc| < 2^16
+  accS += (unsigned long long)(uint32_t)__mul24(cc, cc);
   return qi;
 }
 
@@ -205,99 +241,98 @@ __device__ __forceinline__ unsigned __int128 load_group(const uint8_t* in) {
 }
 
 template <int B>
-__global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a, int32_t m0) {
-  constexpr int L = (1 << B) - 1;
-  // the second pass walks workers and coordinates in the opposite direction of
-  // the first, so it starts on the data the first pass touched last (still
-  // resident in the memory-side cache)
-  const int m = a.reverse ? m0 + (int)(gridDim.y - 1 - blockIdx.y) : m0 + (int)blockIdx.y;
-  const float* g = a.G + (int64_t)m * a.p_stride;
-  const float* h = a.H + (int64_t)m * a.p_stride;
-  uint8_t* out = reinterpret_cast<uint8_t*>(a.codes + (int64_t)m * a.w_stride);
-  __shared__ uint32_t smR[kThreads / 64];
-  {
-    // radius of worker m from the first pass's block partials
-    uint32_t mx = 0;
-    for (int i = threadIdx.x; i < (int)gridDim.x; i += kThreads)
-      mx = max(mx, a.sc.Rpart[(int64_t)m * a.slots + i]);
-    mx = wave_max_u32(mx);
-    if ((threadIdx.x & 63) == 0) smR[threadIdx.x >> 6] = mx;
-    __syncthreads();
-  }
-  const QuantConst c = quant_const<B>(max(max(smR[0], smR[1]), max(smR[2], smR[3])));
-  const int sh = a.eps_K - c.x;
+__global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
   const int64_t nfull = a.p / kGroup;
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const int64_t first = (int64_t)blockIdx.x * a.U * kThreads + threadIdx.x;
+  {
+    const int m = blockIdx.y;
+    const float* g = a.G + (int64_t)m * a.p_stride;
+    const float* h = a.H + (int64_t)m * a.p_stride;
+    uint8_t* out = reinterpret_cast<uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+    uint32_t rbits;
+    if (a.fused_radius) {
+      // at most 64 slots: combine the first pass's maxima here (one launch less)
+      const int lane = threadIdx.x & 63;
+      rbits = lane < (int)gridDim.x ? a.sc.Rpart[(int64_t)m * a.slots + lane] : 0u;
+      rbits = wave_max_u32(rbits);
+    } else {
+      rbits = a.sc.Rfin[m];
+    }
+    const QuantConst c = quant_const<B>(rbits);
+    const int sh = a.eps_K - c.x;
+    double accN = 0.0;
+    unsigned long long accS = 0;
 
-  double accN = 0.0;
-  unsigned long long accS = 0;
-
-  if (c.zero) {
-    for (int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x; grp < nfull; grp += stride)
-      store_group<B>(out + grp * B, 0);
-  } else {
-    for (int64_t g0i = (int64_t)blockIdx.x * kThreads + threadIdx.x; g0i < nfull; g0i += stride) {
-      const int64_t grp = a.reverse ? nfull - 1 - g0i : g0i;
-      const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
-      const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
-      const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
-      const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-      const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-      unsigned __int128 v = 0;
+    if (c.zero) {
+      for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads)
+        store_group<B>(out + grp * B, 0);
+    } else {
+      for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads) {
+        const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
+        const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
+        const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
+        const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+        unsigned __int128 v = 0;
 #pragma unroll
-      for (int j = 0; j < kGroup; ++j)
-        v |= (unsigned __int128)quant_one<B>(gv[j], hv[j], c, sh, accN, accS) << (j * B);
-      store_group<B>(out + grp * B, v);
+        for (int j = 0; j < kGroup; ++j)
+          v |= (unsigned __int128)quant_one<B>(gv[j], hv[j], c, sh, accN, accS) << (j * B);
+        store_group<B>(out + grp * B, v);
+      }
     }
-  }
-  // ragged tail (p % 8 coordinates) and zero fill up to the row stride
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    int64_t byte = nfull * B;
-    if (a.p > nfull * kGroup) {
-      unsigned __int128 v = 0;
-      if (!c.zero)
-        for (int64_t i = nfull * kGroup; i < a.p; ++i)
-          v |= (unsigned __int128)quant_one<B>(g[i], h[i], c, sh, accN, accS)
-               << ((int)(i - nfull * kGroup) * B);
-      for (int k = 0; k < B; ++k) out[byte + k] = (uint8_t)(v >> (8 * k));
-      byte += B;
+    // ragged tail (p % 8 coordinates) and zero fill up to the row stride
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      int64_t byte = nfull * B;
+      if (a.p > nfull * kGroup) {
+        unsigned __int128 v = 0;
+        if (!c.zero)
+          for (int64_t i = nfull * kGroup; i < a.p; ++i)
+            v |= (unsigned __int128)quant_one<B>(g[i], h[i], c, sh, accN, accS)
+                 << ((int)(i - nfull * kGroup) * B);
+        for (int k = 0; k < B; ++k) out[byte + k] = (uint8_t)(v >> (8 * k));
+        byte += B;
+      }
+      for (; byte < a.w_stride * 4; ++byte) out[byte] = 0;
     }
-    for (; byte < a.w_stride * 4; ++byte) out[byte] = 0;
-  }
 
-  // block totals of the two exact integer sums
-  unsigned long long s64 = wave_sum_u64(accS);
-  unsigned long long n64 = wave_sum_u64((unsigned long long)accN);
+    // block totals of the two exact integer sums -> slot blockIdx.x of worker m
+    __shared__ unsigned long long smS[kWavesPerBlock], smN[kWavesPerBlock];
+    const unsigned long long s64 = wave_sum_u64(accS);
+    const unsigned long long n64 = wave_sum_u64((unsigned long long)accN);
+    if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int64_t slot = (int64_t)m * a.slots + blockIdx.x;
+      a.sc.Spart[slot] = (smS[0] + smS[1]) + (smS[2] + smS[3]);
+      a.sc.Npart[slot] = (smN[0] + smN[1]) + (smN[2] + smN[3]);
+    }
+  }
+}
+
+// Totals of the block partials (integers: order-free) and the skip rule
+// (eqs. 7a-7b) in binary64 with a fixed operation order; one block per worker.
+template <int B>
+__global__ __launch_bounds__(kThreads) void decide_kernel(QuantArgs a, int32_t n_slots) {
+  constexpr int L = (1 << B) - 1;
   __shared__ unsigned long long smS[kThreads / 64], smN[kThreads / 64];
-  if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
-  __syncthreads();
-  __shared__ bool last_s;
-  if (threadIdx.x == 0) {
-    a.sc.Spart[(int64_t)m * a.slots + blockIdx.x] = smS[0] + smS[1] + smS[2] + smS[3];
-    a.sc.Npart[(int64_t)m * a.slots + blockIdx.x] = smN[0] + smN[1] + smN[2] + smN[3];
-    __threadfence();
-    last_s = (atomicAdd(&a.sc.ticket[m], 1u) == gridDim.x - 1);
-  }
-  __syncthreads();
-  if (!last_s) return;
-
-  // last block of worker m: totals of the block partials (integers: order-free)
-  __threadfence();
-  s64 = 0; n64 = 0;
-  for (int i = threadIdx.x; i < (int)gridDim.x; i += kThreads) {
-    s64 += __hip_atomic_load(&a.sc.Spart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    n64 += __hip_atomic_load(&a.sc.Npart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __shared__ uint32_t smR[kThreads / 64];
+  const int m = blockIdx.x;
+  unsigned long long s64 = 0, n64 = 0;
+  uint32_t rb = 0;
+  for (int i = threadIdx.x; i < n_slots; i += kThreads) {
+    s64 += a.sc.Spart[(int64_t)m * a.slots + i];
+    n64 += a.sc.Npart[(int64_t)m * a.slots + i];
+    rb = max(rb, a.sc.Rpart[(int64_t)m * a.slots + i]);
   }
   s64 = wave_sum_u64(s64);
   n64 = wave_sum_u64(n64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
+  rb = wave_max_u32(rb);
+  if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; smR[threadIdx.x >> 6] = rb; }
   __syncthreads();
   if (threadIdx.x != 0) return;
   const unsigned long long Sq = smS[0] + smS[1] + smS[2] + smS[3];
   const unsigned long long N = smN[0] + smN[1] + smN[2] + smN[3];
-
-  // skip rule (eqs. 7a-7b), binary64, fixed order
+  const QuantConst c = quant_const<B>(max(max(smR[0], smR[1]), max(smR[2], smR[3])));
   const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
   const double r = (double)c.R / (double)L;
   const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
@@ -322,7 +357,6 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a, int32_t m0
   a.sc.E2[m] = E2;
   a.sc.lhs[m] = lhs;
   a.sc.rhs[m] = rhs;
-  a.sc.ticket[m] = 0;
 }
 
 // ------------------------------------------------------------------ server step
@@ -336,12 +370,18 @@ struct ServerArgs {
   float* theta;
   DeviceScalars sc;
   int64_t p, p_stride, w_stride;
-  int32_t M, D, b;
+  int32_t M, D, b, J;
   float alpha;
 };
 
+constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
+
 // eq. 4: nabla^k = nabla^{k-1} + sum_{m in M^k} deltaQ_m, theta^{k+1} = theta^k - alpha nabla^k,
 // with Q_m(theta_hat_m) += deltaQ_m for the uploading workers (Alg. 2, upload branch).
+// Worker-major: a lane owns up to 4 groups of 8 coordinates for the whole
+// kernel and keeps their running sums in registers, so the grid sweeps one
+// uploading worker's row at a time (one read stream, one write stream) in
+// ascending m -- the order in which the sums are defined.
 template <int B>
 __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   constexpr uint32_t L = (1u << B) - 1u;
@@ -369,53 +409,68 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   const int n_up = n_up_s;
 
   const int64_t nfull = a.p / kGroup;
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
-  double n2 = 0.0;
-  for (int64_t grp = (int64_t)blockIdx.x * kThreads + threadIdx.x; grp < nfull; grp += stride) {
-    float acc[kGroup];
+  const int64_t span = (int64_t)gridDim.x * kThreads;
+  const int64_t grp0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  float acc[kServerJ][kGroup];
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j) acc[j] = 0.0f;
-#pragma unroll 2
-    for (int k = 0; k < n_up; ++k) {
-      const int m = list[k];
-      const float R = Rm[m], step = stepm[m];
-      const unsigned __int128 v =
-          load_group<B>(reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride) + grp * B);
-      float4* hp = reinterpret_cast<float4*>(a.H + (int64_t)m * a.p_stride + grp * kGroup);
-      float4 h0 = hp[0], h1 = hp[1];
-      float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+  for (int j = 0; j < kServerJ; ++j)
 #pragma unroll
-      for (int j = 0; j < kGroup; ++j) {
-        const uint32_t q = (uint32_t)(v >> (j * B)) & L;
-        float dq = (float)q * step;
-        dq = dq - R;
-        hv[j] = hv[j] + dq;
-        acc[j] = acc[j] + dq;
+    for (int i = 0; i < kGroup; ++i) acc[j][i] = 0.0f;
+
+  for (int k = 0; k < n_up; ++k) {
+    const int m = list[k];
+    const float R = Rm[m], step = stepm[m];
+    const uint8_t* crow = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+    float* hrow = a.H + (int64_t)m * a.p_stride;
+#pragma unroll
+    for (int j = 0; j < kServerJ; ++j) {
+      const int64_t grp = grp0 + j * span;
+      if (j < a.J && grp < nfull) {
+        const unsigned __int128 v = load_group<B>(crow + grp * B);
+        float4* hp = reinterpret_cast<float4*>(hrow + grp * kGroup);
+        const float4 h0 = hp[0], h1 = hp[1];
+        float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) {
+          const uint32_t q = (uint32_t)(v >> (i * B)) & L;
+          float dq = (float)q * step;
+          dq = dq - R;
+          hv[i] = hv[i] + dq;
+          acc[j][i] = acc[j][i] + dq;
+        }
+        hp[0] = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        hp[1] = make_float4(hv[4], hv[5], hv[6], hv[7]);
       }
-      hp[0] = make_float4(hv[0], hv[1], hv[2], hv[3]);
-      hp[1] = make_float4(hv[4], hv[5], hv[6], hv[7]);
     }
-    float4* np4 = reinterpret_cast<float4*>(a.nabla + grp * kGroup);
-    float4* tp4 = reinterpret_cast<float4*>(a.theta + grp * kGroup);
-    const float4 n0 = np4[0], n1 = np4[1], t0 = tp4[0], t1 = tp4[1];
-    float nv[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
-    float tv[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+  }
+
+  double n2 = 0.0;
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j) {
-      const float nb = nv[j] + acc[j];
-      nv[j] = nb;
-      const float st = a.alpha * nb;
-      tv[j] = tv[j] - st;
-      n2 = fma((double)nb, (double)nb, n2);
+  for (int j = 0; j < kServerJ; ++j) {
+    const int64_t grp = grp0 + j * span;
+    if (j < a.J && grp < nfull) {
+      float4* np4 = reinterpret_cast<float4*>(a.nabla + grp * kGroup);
+      float4* tp4 = reinterpret_cast<float4*>(a.theta + grp * kGroup);
+      const float4 n0 = np4[0], n1 = np4[1], t0 = tp4[0], t1 = tp4[1];
+      float nv[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
+      float tv[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+#pragma unroll
+      for (int i = 0; i < kGroup; ++i) {
+        const float nb = nv[i] + acc[j][i];
+        nv[i] = nb;
+        const float st = a.alpha * nb;
+        tv[i] = tv[i] - st;
+        n2 = fma((double)nb, (double)nb, n2);
+      }
+      np4[0] = make_float4(nv[0], nv[1], nv[2], nv[3]);
+      np4[1] = make_float4(nv[4], nv[5], nv[6], nv[7]);
+      tp4[0] = make_float4(tv[0], tv[1], tv[2], tv[3]);
+      tp4[1] = make_float4(tv[4], tv[5], tv[6], tv[7]);
     }
-    np4[0] = make_float4(nv[0], nv[1], nv[2], nv[3]);
-    np4[1] = make_float4(nv[4], nv[5], nv[6], nv[7]);
-    tp4[0] = make_float4(tv[0], tv[1], tv[2], tv[3]);
-    tp4[1] = make_float4(tv[4], tv[5], tv[6], tv[7]);
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     for (int64_t i = nfull * kGroup; i < a.p; ++i) {
-      float acc = 0.0f;
+      float acc1 = 0.0f;
       for (int k = 0; k < n_up; ++k) {
         const int m = list[k];
         const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
@@ -426,9 +481,9 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
         dq = dq - Rm[m];
         float* hp = a.H + (int64_t)m * a.p_stride + i;
         *hp = *hp + dq;
-        acc = acc + dq;
+        acc1 = acc1 + dq;
       }
-      const float nb = a.nabla[i] + acc;
+      const float nb = a.nabla[i] + acc1;
       a.nabla[i] = nb;
       const float st = a.alpha * nb;
       a.theta[i] = a.theta[i] - st;
@@ -437,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   }
 
   n2 = wave_sum_f64(n2);
-  __shared__ double smd[kThreads / 64];
+  __shared__ double smd[kThreads];
   __shared__ bool last_s;
   if ((threadIdx.x & 63) == 0) smd[threadIdx.x >> 6] = n2;
   __syncthreads();
@@ -463,12 +518,19 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
     }
   }
   if (my_bits) atomicAdd(a.sc.bits, my_bits);
+  // ||nabla||^2: block partials summed in a fixed order (strided, then a tree)
+  double tot = 0.0;
+  for (unsigned i = threadIdx.x; i < gridDim.x; i += kThreads)
+    tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  smd[threadIdx.x] = tot;
+  __syncthreads();
+  for (int off = kThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) smd[threadIdx.x] += smd[threadIdx.x + off];
+    __syncthreads();
+  }
   if (threadIdx.x == 0) {
-    double tot = 0.0;
-    for (unsigned i = 0; i < gridDim.x; ++i)
-      tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int d = a.D - 1; d > 0; --d) a.sc.dtheta2[d] = a.sc.dtheta2[d - 1];
-    a.sc.dtheta2[0] = ((double)a.alpha * (double)a.alpha) * tot;
+    a.sc.dtheta2[0] = ((double)a.alpha * (double)a.alpha) * smd[0];
     *a.sc.srv_ticket = 0;
   }
 }
@@ -482,16 +544,43 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
 
 struct Layout {
   size_t H, nabla, scalars, total;
-  size_t Rpart, Spart, Npart, ticket, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
+  size_t Rpart, Spart, Npart, Rfin, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
       dtheta2, xi, srv_part, scalars_end;
 };
 
-// Block-partial slots per worker in the two streaming passes.
+// Server step: J groups per lane (at most kServerJ), enough blocks to cover p.
+static int64_t server_blocks(int64_t p, int32_t* J_out) {
+  const int64_t nfull = p / kGroup;
+  int64_t T = (nfull + kThreads - 1) / kThreads;
+  if (T < 1) T = 1;
+  int64_t J = (T + 2047) / 2048;
+  if (J > kServerJ) J = kServerJ;
+  if (J < 1) J = 1;
+  if (J_out) *J_out = (int32_t)J;
+  return (T + J - 1) / J;
+}
+
+// Upper bound of block-partial slots per worker in the two streaming passes.
 static int32_t partial_slots(int32_t M) {
-  if (M <= 64) return 2048;
-  const int32_t s = 131072 / M;
+  if (M <= 64) return kMaxSlots;
+  const int32_t s = 524288 / M;
   return s < 32 ? 32 : s;
 }
+
+// Grid of the two streaming passes: Gx blocks per worker, U tiles per block.
+static Sweep make_sweep(int64_t p, int32_t M) {
+  Sweep sw;
+  sw.nfull = p / kGroup;
+  sw.T = (sw.nfull + kThreads - 1) / kThreads;
+  if (sw.T < 1) sw.T = 1;
+  const int64_t max_gx = partial_slots(M);
+  sw.U = (int32_t)((sw.T + max_gx - 1) / max_gx);
+  sw.Gx = (int32_t)((sw.T + sw.U - 1) / sw.U);
+  return sw;
+}
+
+// Slots actually used (and allocated) per worker.
+static int32_t used_slots(int64_t p, int32_t M) { return make_sweep(p, M).Gx; }
 
 static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   Layout l{};
@@ -501,11 +590,11 @@ static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   l.H = take((size_t)M * ps * sizeof(float));
   l.nabla = take((size_t)ps * sizeof(float));
   l.scalars = off;
-  const size_t slots = (size_t)partial_slots(M);
+  const size_t slots = (size_t)used_slots(p, M);
   l.Rpart = take((size_t)M * slots * 4);
   l.Spart = take((size_t)M * slots * 8);
   l.Npart = take((size_t)M * slots * 8);
-  l.ticket = take((size_t)M * 4);
+  l.Rfin = take((size_t)M * 4);
   l.Sq = take((size_t)M * 8);
   l.E2 = take((size_t)M * 8);
   l.lhs = take((size_t)M * 8);
@@ -518,7 +607,7 @@ static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   l.srv_ticket = take(4);
   l.dtheta2 = take((size_t)D * 8);
   l.xi = take((size_t)D * 8);
-  l.srv_part = take((size_t)kMaxServerBlocks * 8);
+  l.srv_part = take((size_t)server_blocks(p, nullptr) * 8);
   l.scalars_end = off;
   l.total = off;
   return l;
@@ -533,8 +622,9 @@ static bool valid_sizes(int32_t M, int64_t p, int32_t b, int32_t D) {
 }
 
 template <int B>
-static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a, int32_t m0) {
-  hipLaunchKernelGGL(codes_kernel<B>, grid, dim3(kThreads), 0, s, a, m0);
+static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
+  hipLaunchKernelGGL(codes_kernel<B>, grid, dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(decide_kernel<B>, dim3((unsigned)a.M), dim3(kThreads), 0, s, a, (int32_t)grid.x);
 }
 template <int B>
 static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArgs& a) {
@@ -551,23 +641,6 @@ static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArg
     case 16: CALL(16); break;                                                                     \
     default: break;                                                                               \
   }
-
-// Blocks per worker for the streaming passes: enough blocks to fill the chip,
-// and at most 512 groups (4096 coordinates) per lane so that the per-lane
-// binary64 partial of the integer error sum stays below 2^53.
-static int blocks_per_worker(int64_t p, int32_t n_workers, int n_cu, int32_t slots) {
-  const int64_t nfull = p / kGroup;
-  int64_t by_work = (nfull + kThreads - 1) / kThreads;         // one group per lane
-  if (by_work < 1) by_work = 1;
-  int64_t want = ((int64_t)n_cu * 8 + n_workers - 1) / n_workers;   // ~8 blocks per CU in total
-  if (want < 1) want = 1;
-  int64_t bpw = by_work < want ? by_work : want;
-  const int64_t min_bpw = (nfull + (int64_t)kThreads * 512 - 1) / ((int64_t)kThreads * 512);
-  if (bpw < min_bpw) bpw = min_bpw;
-  if (bpw > slots) bpw = slots;
-  if (bpw < 1) bpw = 1;
-  return (int)bpw;
-}
 
 }  // namespace laq
 
@@ -630,7 +703,7 @@ int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const 
   s.Rpart = (uint32_t*)(w + l.Rpart);
   s.Spart = (unsigned long long*)(w + l.Spart);
   s.Npart = (unsigned long long*)(w + l.Npart);
-  s.ticket = (uint32_t*)(w + l.ticket);
+  s.Rfin = (uint32_t*)(w + l.Rfin);
   s.Sq = (long long*)(w + l.Sq);
   s.E2 = (double*)(w + l.E2);
   s.lhs = (double*)(w + l.lhs);
@@ -652,18 +725,6 @@ int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const 
   e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
   if (e != hipSuccess || n_cu <= 0) return fail(LAQ_EDEVICE);
   ctx->n_cu = n_cu;
-
-  // workers per quantize launch pair: keep one pair's operands (g and h rows)
-  // within a budget that the memory-side cache can hold between the two passes
-  long long budget_mb = 96;
-  if (const char* env = getenv("LAQ_GROUP_MB")) { long long v = atoll(env); if (v > 0) budget_mb = v; }
-  int64_t per_worker = ctx->p_stride * 8;
-  int64_t gw = (budget_mb << 20) / (per_worker > 0 ? per_worker : 1);
-  if (gw < 1) gw = 1;
-  if (gw > M) gw = M;
-  ctx->group_workers = gw;
-  ctx->reverse_pass2 = 1;
-  if (const char* env = getenv("LAQ_REVERSE")) ctx->reverse_pass2 = atoi(env) ? 1 : 0;
 
   double xi64[4096];
   for (int d = 0; d < D; ++d) xi64[d] = (double)xi[d];
@@ -700,19 +761,20 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   a.sc = ctx->sc;
   a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
   a.M = ctx->M; a.D = ctx->D; a.t_bar = ctx->t_bar; a.eps_K = ctx->eps_K;
-  a.slots = partial_slots(ctx->M);
-  a.reverse = ctx->reverse_pass2;
+  a.slots = used_slots(ctx->p, ctx->M);
   a.alpha = ctx->alpha; a.mode = ctx->mode;
-  for (int32_t m0 = 0; m0 < ctx->M; m0 += (int32_t)ctx->group_workers) {
-    const int32_t nw = (int32_t)((ctx->M - m0) < ctx->group_workers ? (ctx->M - m0) : ctx->group_workers);
-    const int bpw = blocks_per_worker(ctx->p, nw, ctx->n_cu, a.slots);
-    const dim3 grid((unsigned)bpw, (unsigned)nw);
-    hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
-                       ctx->p_stride, m0, a.slots, ctx->sc.Rpart);
-#define LAQ_CALL(BB) launch_codes<BB>(grid, ctx->stream, a, m0)
-    LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
+  const Sweep sw = make_sweep(ctx->p, ctx->M);
+  const dim3 grid((unsigned)sw.Gx, (unsigned)ctx->M);
+  a.U = sw.U;
+  hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
+                     ctx->p_stride, sw.U, a.slots, ctx->sc);
+  a.fused_radius = sw.Gx <= 64;
+  if (!a.fused_radius)
+    hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
+                       sw.Gx, a.slots, ctx->sc);
+#define LAQ_CALL(BB) launch_codes<BB>(grid, ctx->stream, a)
+  LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
 #undef LAQ_CALL
-  }
   LAQ_HIP(ctx, hipGetLastError());
   return LAQ_OK;
 }
@@ -729,11 +791,7 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
   a.H = ctx->H; a.nabla = ctx->nabla; a.theta = theta_dev; a.sc = ctx->sc;
   a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
   a.M = ctx->M; a.D = ctx->D; a.b = ctx->b; a.alpha = ctx->alpha;
-  const int64_t nfull = ctx->p / kGroup;
-  int64_t blocks = (nfull + kThreads - 1) / kThreads;
-  const int64_t cap = (int64_t)ctx->n_cu * 8 < kMaxServerBlocks ? (int64_t)ctx->n_cu * 8 : kMaxServerBlocks;
-  if (blocks > cap) blocks = cap;
-  if (blocks < 1) blocks = 1;
+  const int64_t blocks = server_blocks(ctx->p, &a.J);
   const size_t smem = (size_t)ctx->M * 12;
   const dim3 grid((unsigned)blocks);
 #define LAQ_CALL(BB) launch_server<BB>(grid, smem, ctx->stream, a)

@@ -11,14 +11,13 @@ namespace laq {
 
 constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes
 constexpr int kGroup = 8;              // elements owned by one lane per step: 8*b bits = b whole bytes
-constexpr int kMaxServerBlocks = 4096; // partial sums of ||nabla||^2
 
 // Per-worker and global scalars kept in the device workspace.
 struct DeviceScalars {
   uint32_t* Rpart;              // [M][slots] block maxima of |g-h| (raw bits)
   unsigned long long* Spart;    // [M][slots] block sums of (2q-L)^2
   unsigned long long* Npart;    // [M][slots] block sums of the integer error squares
-  uint32_t* ticket;             // [M] blocks finished for worker m (reset after use)
+  uint32_t* Rfin;               // [M] radius of the current call (raw bits)
   long long* Sq;                // [M] stash
   double* E2;                   // [M] stash
   double* lhs;                  // [M]
@@ -31,7 +30,7 @@ struct DeviceScalars {
   uint32_t* srv_ticket;         // [1]
   double* dtheta2;              // [D]
   double* xi;                   // [D]
-  double* srv_part;             // [kMaxServerBlocks]
+  double* srv_part;             // [server blocks] partial sums of ||nabla||^2
 };
 
 struct Mlp {
@@ -59,8 +58,6 @@ struct laq_ctx {
   float* nabla = nullptr;
   laq::DeviceScalars sc{};
   size_t scalars_offset = 0, scalars_bytes = 0;
-  int64_t group_workers = 0;     // workers per quantize launch pair (cache residency)
-  int32_t reverse_pass2 = 1;     // second pass walks the data backwards
 
   // model
   int32_t kind = LAQ_MODEL_NONE;

@@ -153,16 +153,20 @@ def test_nonfinite_radius_sets_the_status_word():
     assert msgs[2].cpu().numpy()[1] == 0         # the faulty worker is not aggregated
 
 
-def test_worker_groups_smaller_than_M(monkeypatch):
-    """Workers are quantized in several launch pairs when their rows exceed the cache budget."""
-    monkeypatch.setenv("LAQ_GROUP_MB", "1")
-    M, p, b = 7, 60_000, 4                      # 480 KB per worker -> 2 workers per pair
-    rng = np.random.default_rng(9)
+def test_more_tiles_than_blocks_per_worker():
+    """p large enough that every block sweeps several tiles of each worker and
+    several workers in turn (the launch shape of the full-size workloads)."""
+    M, p, b = 3, 5_000_003, 4
     ctx, st, theta = make_pair(M, p, b, D=5, t_bar=10)
-    G = rng.standard_normal((M, p)).astype(np.float32)
+    scales = laq_synth.worker_scales(M)
+    G = laq_synth.host_gradients(M, p, scales=scales)
     Gd = to_dev_G(ctx, G)
-    msgs, _ = check_quantize(ctx, st, Gd, G)
-    check_server(ctx, st, theta, msgs, G)
+    for it in range(2):
+        msgs, _ = check_quantize(ctx, st, Gd, G)
+        check_server(ctx, st, theta, msgs, G)
+        push_state(ctx, st)
+        G = laq_synth.host_drift(G, it, scales=scales)
+        Gd[:, :p].copy_(torch.from_numpy(G))
 
 
 def test_bad_arguments_are_rejected():

@@ -1,13 +1,492 @@
 // Worker gradients of the fully connected ReLU network (supplement,
-// "Simulation details"): placeholder until the MFMA path lands.
+// "Simulation details"): forward, softmax cross-entropy, backward, for all M
+// workers at once.  theta = (W_1[d0][d1], b_1[d1], W_2, b_2, ...) is shared, so
+// the forward and the activation-gradient products are single GEMMs over all
+// S = M*N_m samples; only the weight gradients are per worker (a GEMM batched
+// over m, written straight into row m of G with the 1/N scale and the
+// regulariser share (N_m/N) lambda theta applied in the epilogue).
+//
+// Dense products run on the fp32 matrix cores (v_mfma_f32_32x32x2_f32):
+// 128x128 block tile, 16-deep K tile staged through LDS in K-major order so
+// that every MFMA operand fetch is a conflict-free ds_read_b32, 4 wavefronts
+// of 64x64 each, next tile prefetched into registers while the current one is
+// multiplied.  The class layer (C <= 16 columns) is too narrow for a matrix
+// tile and is bandwidth-bound: plain VALU kernels, one read of the activations.
+#include <math.h>
+
 #include "laq_internal.h"
 
 namespace laq {
 
-size_t mlp_workspace_bytes(const laq_ctx*, int64_t) { return 256; }
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-int mlp_worker_grads(laq_ctx* ctx, const float*, float*) {
-  return set_error(ctx, LAQ_ESTATE, "MLP gradients are not built into this library yet");
+constexpr int kBM = 128, kBN = 128, kBK = 16, kLd = kBM + 4;
+
+enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2 };
+
+struct GemmArgs {
+  const float* A;      // TA ? [K][M] : [M][K]
+  const float* B;      // TB ? [N][K] : [K][N]
+  float* C;            // [M][N]
+  int32_t M, N, K;
+  int64_t lda, ldb, ldc;
+  int64_t sA, sB, sC;  // batch strides (elements) for blockIdx.z
+  int32_t vecA, vecB;  // operand rows are 16-byte aligned
+  const float* aux;    // bias[N] | mask[M][ldaux] | W[M][ldaux]
+  int64_t ldaux;
+  float scale, reg;
+};
+
+// K-major source S[k][x] -> LDS tile[kk][xx]
+__device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, int X, int k0, int x0,
+                                            int vec, float4 (&r)[2]) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int kk = t / 32 + 8 * i, xx = (t % 32) * 4;
+    const int k = k0 + kk, x = x0 + xx;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < K) {
+      const float* src = S + (int64_t)k * ld + x;
+      if (vec && x + 3 < X) {
+        v = *reinterpret_cast<const float4*>(src);
+      } else {
+        if (x < X) v.x = src[0];
+        if (x + 1 < X) v.y = src[1];
+        if (x + 2 < X) v.z = src[2];
+        if (x + 3 < X) v.w = src[3];
+      }
+    }
+    r[i] = v;
+  }
+}
+__device__ __forceinline__ void store_direct(float (*tile)[kLd], const float4 (&r)[2]) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int kk = t / 32 + 8 * i, xx = (t % 32) * 4;
+    *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
+  }
+}
+
+// X-major source S[x][k] -> LDS tile[kk][xx] (transposed on the way in)
+__device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int K, int X, int k0, int x0,
+                                                int vec, float4 (&r)[2]) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int xx = t / 4 + 64 * i, kk = (t % 4) * 4;
+    const int k = k0 + kk, x = x0 + xx;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (x < X) {
+      const float* src = S + (int64_t)x * ld + k;
+      if (vec && k + 3 < K) {
+        v = *reinterpret_cast<const float4*>(src);
+      } else {
+        if (k < K) v.x = src[0];
+        if (k + 1 < K) v.y = src[1];
+        if (k + 2 < K) v.z = src[2];
+        if (k + 3 < K) v.w = src[3];
+      }
+    }
+    r[i] = v;
+  }
+}
+__device__ __forceinline__ void store_transposed(float (*tile)[kLd], const float4 (&r)[2]) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int xx = t / 4 + 64 * i, kk = (t % 4) * 4;
+    tile[kk + 0][xx] = r[i].x;
+    tile[kk + 1][xx] = r[i].y;
+    tile[kk + 2][xx] = r[i].z;
+    tile[kk + 3][xx] = r[i].w;
+  }
+}
+
+template <bool TA, bool TB, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) float As[kBK][kLd];
+  __shared__ __attribute__((aligned(16))) float Bs[kBK][kLd];
+  const float* A = g.A + (int64_t)blockIdx.z * g.sA;
+  const float* B = g.B + (int64_t)blockIdx.z * g.sB;
+  float* C = g.C + (int64_t)blockIdx.z * g.sC;
+  const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wy = wave >> 1, wx = wave & 1;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  float4 ra[2], rb[2];
+  auto fetch = [&](int k0) {
+    if (TA) load_direct(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    else load_transposed(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    if (TB) load_transposed(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    else load_direct(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+  };
+  auto stage = [&]() {
+    if (TA) store_direct(As, ra); else store_transposed(As, ra);
+    if (TB) store_transposed(Bs, rb); else store_direct(Bs, rb);
+  };
+
+  fetch(0);
+  stage();
+  __syncthreads();
+  const int kh = lane >> 5, li = lane & 31;
+  for (int k0 = 0; k0 < g.K; k0 += kBK) {
+    const bool more = k0 + kBK < g.K;
+    if (more) fetch(k0 + kBK);
+#pragma unroll
+    for (int kk = 0; kk < kBK; kk += 2) {
+      const float a0 = As[kk + kh][wy * 64 + li];
+      const float a1 = As[kk + kh][wy * 64 + 32 + li];
+      const float b0 = Bs[kk + kh][wx * 64 + li];
+      const float b1 = Bs[kk + kh][wx * 64 + 32 + li];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    __syncthreads();
+    if (more) {
+      stage();
+      __syncthreads();
+    }
+  }
+
+  // epilogue: lane holds C[i][j], j = lane%32, i = 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+  for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+    for (int tj = 0; tj < 2; ++tj) {
+      const int col = n0 + wx * 64 + tj * 32 + li;
+      if (col >= g.N) continue;
+      float bias = 0.0f;
+      if (EPI == EPI_BIAS_RELU) bias = g.aux[col];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wy * 64 + ti * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+        if (row >= g.M) continue;
+        float v = acc[ti][tj][r];
+        if (EPI == EPI_BIAS_RELU) {
+          v = fmaxf(v + bias, 0.0f);
+        } else if (EPI == EPI_MASK) {
+          v = g.aux[(int64_t)row * g.ldaux + col] > 0.0f ? v : 0.0f;
+        } else {
+          v = fmaf(v, g.scale, g.reg * g.aux[(int64_t)row * g.ldaux + col]);
+        }
+        C[(int64_t)row * g.ldc + col] = v;
+      }
+    }
+}
+
+// ------------------------------------------------------------------ class layer (C <= 16)
+
+constexpr int kCMax = 16;
+
+// logits z = a W + b, P = softmax(z), dZ = P - onehot(y); one wavefront per row.
+// W[K][C] is staged in LDS; lanes split K.
+__global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __restrict__ Aact, int64_t lda,
+                                                                 const float* __restrict__ W,
+                                                                 const float* __restrict__ bias,
+                                                                 const int32_t* __restrict__ y, int64_t S,
+                                                                 int32_t K, int32_t C,
+                                                                 float* __restrict__ dZ) {
+  extern __shared__ float Ws[];   // [K][C]
+  for (int i = threadIdx.x; i < K * C; i += kThreads) Ws[i] = W[i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t stride = (int64_t)gridDim.x * (kThreads / 64);
+  for (int64_t row = (int64_t)blockIdx.x * (kThreads / 64) + wave; row < S; row += stride) {
+    const float* a = Aact + row * lda;
+    float z[kCMax];
+#pragma unroll
+    for (int c = 0; c < kCMax; ++c) z[c] = 0.0f;
+    for (int k = lane; k < K; k += 64) {
+      const float av = a[k];
+      const float* w = Ws + k * C;
+#pragma unroll
+      for (int c = 0; c < kCMax; ++c)
+        if (c < C) z[c] = fmaf(av, w[c], z[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < kCMax; ++c)
+      if (c < C) {
+        float v = z[c];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+        z[c] = v + bias[c];
+      }
+    float zmax = z[0];
+#pragma unroll
+    for (int c = 1; c < kCMax; ++c)
+      if (c < C) zmax = fmaxf(zmax, z[c]);
+    float den = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kCMax; ++c)
+      if (c < C) { z[c] = expf(z[c] - zmax); den += z[c]; }
+    const float inv = 1.0f / den;
+    const int label = y[row];
+    if (lane == 0) {
+#pragma unroll
+      for (int c = 0; c < kCMax; ++c)
+        if (c < C) dZ[row * C + c] = z[c] * inv - (c == label ? 1.0f : 0.0f);
+    }
+  }
+}
+
+// dZ_prev[n][i] = (A[n][i] > 0) ? sum_c dZ[n][c] W[i][c] : 0      (K = width of the hidden layer)
+__global__ __launch_bounds__(kThreads) void class_backward_kernel(const float* __restrict__ dZ,
+                                                                  const float* __restrict__ W,
+                                                                  const float* __restrict__ Aact, int64_t lda,
+                                                                  int64_t S, int32_t K, int32_t C,
+                                                                  float* __restrict__ dZprev, int64_t ldo) {
+  // block: 256 consecutive hidden units i, loops over rows
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  float w[kCMax];
+#pragma unroll
+  for (int c = 0; c < kCMax; ++c) w[c] = (i < K && c < C) ? W[(int64_t)i * C + c] : 0.0f;
+  for (int64_t n = blockIdx.y; n < S; n += gridDim.y) {
+    const float* dz = dZ + n * C;
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kCMax; ++c)
+      if (c < C) s = fmaf(dz[c], w[c], s);
+    if (i < K) dZprev[n * ldo + i] = Aact[n * lda + i] > 0.0f ? s : 0.0f;
+  }
+}
+
+// Weight gradient of the class layer for worker m and row slab blockIdx.y:
+// part[m][slab][i][c] = sum_{n in slab} A[n][i] dZ[n][c]
+__global__ __launch_bounds__(kThreads) void class_wgrad_kernel(const float* __restrict__ Aact, int64_t lda,
+                                                               const float* __restrict__ dZ, int64_t N_m,
+                                                               int32_t K, int32_t C, int32_t rows_per_slab,
+                                                               float* __restrict__ part) {
+  const int m = blockIdx.z, slab = blockIdx.y;
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  const int64_t r0 = (int64_t)m * N_m + (int64_t)slab * rows_per_slab;
+  int64_t r1 = r0 + rows_per_slab;
+  const int64_t rend = (int64_t)(m + 1) * N_m;
+  if (r1 > rend) r1 = rend;
+  float acc[kCMax];
+#pragma unroll
+  for (int c = 0; c < kCMax; ++c) acc[c] = 0.0f;
+  for (int64_t n = r0; n < r1; ++n) {
+    const float av = (i < K) ? Aact[n * lda + i] : 0.0f;
+    const float* dz = dZ + n * C;
+#pragma unroll
+    for (int c = 0; c < kCMax; ++c)
+      if (c < C) acc[c] = fmaf(av, dz[c], acc[c]);
+  }
+  if (i < K) {
+    float* out = part + (((int64_t)m * gridDim.y + slab) * K + i) * C;
+#pragma unroll
+    for (int c = 0; c < kCMax; ++c)
+      if (c < C) out[c] = acc[c];
+  }
+}
+
+// G[m][off + j] = (sum over slabs, ascending) part[m][slab][j] * scale + reg * theta[off + j]
+__global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __restrict__ part, int32_t n_slab,
+                                                               int64_t len, const float* __restrict__ theta_seg,
+                                                               float scale, float reg, float* __restrict__ G,
+                                                               int64_t p_stride) {
+  const int m = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= len) return;
+  const float* pm = part + (int64_t)m * n_slab * len;
+  float s = 0.0f;
+  for (int k = 0; k < n_slab; ++k) s += pm[(int64_t)k * len + j];
+  G[(int64_t)m * p_stride + j] = fmaf(s, scale, reg * theta_seg[j]);
+}
+
+// Bias gradient: column sums of dZ over a slab of rows of worker m.
+__global__ __launch_bounds__(kThreads) void colsum_kernel(const float* __restrict__ dZ, int64_t ld, int64_t N_m,
+                                                          int32_t width, int32_t rows_per_slab,
+                                                          float* __restrict__ part) {
+  const int m = blockIdx.z, slab = blockIdx.y;
+  const int j = blockIdx.x * kThreads + threadIdx.x;
+  const int64_t r0 = (int64_t)m * N_m + (int64_t)slab * rows_per_slab;
+  int64_t r1 = r0 + rows_per_slab;
+  const int64_t rend = (int64_t)(m + 1) * N_m;
+  if (r1 > rend) r1 = rend;
+  if (j >= width) return;
+  float s = 0.0f;
+  for (int64_t n = r0; n < r1; ++n) s += dZ[n * ld + j];
+  part[((int64_t)m * gridDim.y + slab) * width + j] = s;
+}
+
+// ------------------------------------------------------------------ host side
+
+static inline int64_t align_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+struct MlpPlan {
+  int64_t S;
+  int64_t act_off[LAQ_MAX_LAYERS];   // activations after hidden layer l (l = 1..L-1), floats
+  int64_t dz_off[LAQ_MAX_LAYERS];    // gradients w.r.t. pre-activations of hidden layer l
+  int64_t dzc_off;                   // [S][C]
+  int64_t part_off;                  // slab partial sums
+  int32_t n_slab, rows_per_slab;
+  int64_t total_floats;
+};
+
+static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
+  const Mlp& n = ctx->mlp;
+  MlpPlan pl{};
+  pl.S = (int64_t)ctx->M * N_m;
+  int64_t off = 0;
+  for (int l = 1; l < n.n_layers; ++l) {
+    pl.act_off[l] = off; off += align_up(pl.S * n.dims[l], 64);
+    pl.dz_off[l] = off; off += align_up(pl.S * n.dims[l], 64);
+  }
+  pl.dzc_off = off; off += align_up(pl.S * n.dims[n.n_layers], 64);
+  // slabs of rows for the bandwidth-bound reductions (class-layer weights, biases)
+  int64_t want = ((int64_t)ctx->n_cu * 2 + ctx->M - 1) / ctx->M;
+  if (want < 1) want = 1;
+  int64_t rps = (N_m + want - 1) / want;
+  if (rps < 32) rps = 32;
+  if (rps > N_m) rps = N_m;
+  pl.rows_per_slab = (int32_t)rps;
+  pl.n_slab = (int32_t)((N_m + rps - 1) / rps);
+  int64_t widest = 0;
+  for (int l = 1; l <= n.n_layers; ++l) widest = widest > n.dims[l] ? widest : n.dims[l];
+  const int64_t last_w = (int64_t)n.dims[n.n_layers - 1] * n.dims[n.n_layers];
+  const int64_t part_len = last_w > widest ? last_w : widest;
+  pl.part_off = off; off += align_up((int64_t)ctx->M * pl.n_slab * part_len, 64);
+  pl.total_floats = off;
+  return pl;
+}
+
+size_t mlp_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
+  return (size_t)make_plan(ctx, N_m).total_floats * sizeof(float) + 256;
+}
+
+template <bool TA, bool TB, int EPI>
+static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch) {
+  const dim3 grid((unsigned)((g.N + kBN - 1) / kBN), (unsigned)((g.M + kBM - 1) / kBM), (unsigned)batch);
+  hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI>), grid, dim3(kThreads), 0, ctx->stream, g);
+}
+
+static inline int vec_ok(const void* p, int64_t ld) { return (((uintptr_t)p & 15) == 0 && (ld & 3) == 0) ? 1 : 0; }
+
+int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
+  const Mlp& n = ctx->mlp;
+  const int L = n.n_layers;
+  const int C = n.dims[L];
+  if (C > kCMax) return set_error(ctx, LAQ_EINVAL, "MLP: at most %d classes (got %d)", kCMax, C);
+  const int64_t N_m = ctx->N_m;
+  const MlpPlan pl = make_plan(ctx, N_m);
+  float* ws = reinterpret_cast<float*>(ctx->model_ws);
+  const int64_t S = pl.S;
+  const int64_t N = S;
+  const float inv_N = (float)(1.0 / (double)N);
+  const float reg = (float)(((double)N_m / (double)N) * (double)ctx->lambda);
+  const size_t class_smem = (size_t)n.dims[L - 1] * C * sizeof(float);
+  if (class_smem > 150 * 1024)
+    return set_error(ctx, LAQ_EINVAL, "MLP: last hidden width * classes must fit 150 KB of LDS");
+
+  // ---- forward through the hidden layers: A_l = relu(A_{l-1} W_l + b_l)
+  const float* Ain = ctx->X;
+  int64_t ld_in = ctx->ldx;
+  for (int l = 1; l < L; ++l) {
+    GemmArgs g{};
+    g.A = Ain; g.lda = ld_in;
+    g.B = theta + n.offW[l - 1]; g.ldb = n.dims[l];
+    g.C = ws + pl.act_off[l]; g.ldc = n.dims[l];
+    g.M = (int32_t)S; g.N = n.dims[l]; g.K = n.dims[l - 1];
+    g.vecA = vec_ok(g.A, g.lda); g.vecB = vec_ok(g.B, g.ldb);
+    g.aux = theta + n.offB[l - 1];
+    if (S > 0x7fffffff) return set_error(ctx, LAQ_EINVAL, "MLP: too many samples");
+    launch_gemm<false, false, EPI_BIAS_RELU>(ctx, g, 1);
+    Ain = g.C; ld_in = g.ldc;
+  }
+  // ---- class layer forward + softmax cross-entropy: dZ_L = P - Y
+  float* dZc = ws + pl.dzc_off;
+  {
+    int64_t blocks = (S + 3) / 4;
+    const int64_t cap = (int64_t)ctx->n_cu * 8;
+    if (blocks > cap) blocks = cap;
+    if (class_smem > 48 * 1024)
+      LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(class_forward_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)class_smem));
+    hipLaunchKernelGGL(class_forward_kernel, dim3((unsigned)blocks), dim3(kThreads), class_smem, ctx->stream,
+                       Ain, ld_in, theta + n.offW[L - 1], theta + n.offB[L - 1], ctx->y, S, n.dims[L - 1], C, dZc);
+  }
+  float* part = ws + pl.part_off;
+  // ---- class layer gradients
+  {
+    const int K = n.dims[L - 1];
+    const dim3 wg((unsigned)((K + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
+    hipLaunchKernelGGL(class_wgrad_kernel, wg, dim3(kThreads), 0, ctx->stream, Ain, ld_in, dZc, N_m, K, C,
+                       pl.rows_per_slab, part);
+    const int64_t len = (int64_t)K * C;
+    hipLaunchKernelGGL(slab_finish_kernel, dim3((unsigned)((len + kThreads - 1) / kThreads), (unsigned)ctx->M),
+                       dim3(kThreads), 0, ctx->stream, part, pl.n_slab, len, theta + n.offW[L - 1], inv_N, reg,
+                       G + n.offW[L - 1], ctx->p_stride);
+    const dim3 cg((unsigned)((C + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
+    hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZc, (int64_t)C, N_m, C,
+                       pl.rows_per_slab, part);
+    hipLaunchKernelGGL(slab_finish_kernel, dim3((unsigned)((C + kThreads - 1) / kThreads), (unsigned)ctx->M),
+                       dim3(kThreads), 0, ctx->stream, part, pl.n_slab, (int64_t)C, theta + n.offB[L - 1], inv_N,
+                       reg, G + n.offB[L - 1], ctx->p_stride);
+  }
+  // ---- backward through the hidden layers
+  const float* dZnext = dZc;     // gradient w.r.t. pre-activations of layer l+1
+  for (int l = L - 1; l >= 1; --l) {
+    float* dZl = ws + pl.dz_off[l];
+    const float* Al = ws + pl.act_off[l];
+    const int width = n.dims[l];
+    if (l == L - 1) {
+      int64_t rows = S < 4096 ? S : 4096;
+      const dim3 bg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)rows);
+      hipLaunchKernelGGL(class_backward_kernel, bg, dim3(kThreads), 0, ctx->stream, dZnext,
+                         theta + n.offW[L - 1], Al, (int64_t)width, S, width, C, dZl, (int64_t)width);
+    } else {
+      // dZ_l = (dZ_{l+1} W_{l+1}^T) .* (A_l > 0)
+      GemmArgs g{};
+      g.A = dZnext; g.lda = n.dims[l + 1];
+      g.B = theta + n.offW[l]; g.ldb = n.dims[l + 1];    // W_{l+1}[d_l][d_{l+1}] read as [N][K]
+      g.C = dZl; g.ldc = width;
+      g.M = (int32_t)S; g.N = width; g.K = n.dims[l + 1];
+      g.vecA = vec_ok(g.A, g.lda); g.vecB = vec_ok(g.B, g.ldb);
+      g.aux = Al; g.ldaux = width;
+      launch_gemm<false, true, EPI_MASK>(ctx, g, 1);
+    }
+    // dW_l(m) = A_{l-1}(m)^T dZ_l(m), scaled, + regulariser -> G[m][offW_{l-1}]
+    {
+      const float* Aprev = (l == 1) ? ctx->X : ws + pl.act_off[l - 1];
+      const int64_t ldp = (l == 1) ? ctx->ldx : n.dims[l - 1];
+      GemmArgs g{};
+      g.A = Aprev; g.lda = ldp; g.sA = N_m * ldp;
+      g.B = dZl; g.ldb = width; g.sB = N_m * (int64_t)width;
+      g.C = G + n.offW[l - 1]; g.ldc = width; g.sC = ctx->p_stride;
+      g.M = n.dims[l - 1]; g.N = width; g.K = (int32_t)N_m;
+      g.vecA = vec_ok(g.A, g.lda) && ((g.sA & 3) == 0);
+      g.vecB = vec_ok(g.B, g.ldb) && ((g.sB & 3) == 0);
+      g.aux = theta + n.offW[l - 1]; g.ldaux = width;
+      g.scale = inv_N; g.reg = reg;
+      launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
+    }
+    // db_l(m) = column sums of dZ_l(m)
+    {
+      const dim3 cg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
+      hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZl, (int64_t)width, N_m, width,
+                         pl.rows_per_slab, part);
+      hipLaunchKernelGGL(slab_finish_kernel,
+                         dim3((unsigned)((width + kThreads - 1) / kThreads), (unsigned)ctx->M), dim3(kThreads), 0,
+                         ctx->stream, part, pl.n_slab, (int64_t)width, theta + n.offB[l - 1], inv_N, reg,
+                         G + n.offB[l - 1], ctx->p_stride);
+    }
+    dZnext = dZl;
+  }
+  LAQ_HIP(ctx, hipGetLastError());
+  return LAQ_OK;
 }
 
 }  // namespace laq

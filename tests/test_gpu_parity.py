@@ -249,3 +249,42 @@ def test_full_loop_on_the_smallest_workload():
         skipped += int((out["upload"] == 0).sum())
         push_state(ctx, st)
     assert skipped > w.iterations          # lazy aggregation is active on this problem
+
+
+@pytest.mark.parametrize("dims,N_m,M", [((20, 16, 12, 5), 33, 2), ((30, 7), 50, 3), ((784, 200, 10), 300, 3),
+                                        ((130, 257, 129, 10), 259, 2), ((64, 128, 16), 128, 1),
+                                        ((784, 512, 256, 10), 512, 2)])
+def test_mlp_gradients_match_the_oracle(dims, N_m, M):
+    w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, M, N_m, dims, laq_synth.mlp_param_count(dims), 8)
+    G, G_ref = _grad_case(w)
+    err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
+    assert err.max() <= 1e-5, err
+    # every layer separately, so a small layer cannot hide behind a large one
+    off = 0
+    for i in range(len(dims) - 1):
+        for n in (dims[i] * dims[i + 1], dims[i + 1]):
+            seg, ref = G[:, off:off + n], G_ref[:, off:off + n]
+            assert np.abs(seg - ref).max() <= 2e-5 * np.abs(ref).max(), (i, n)
+            off += n
+
+
+def test_full_loop_on_a_scaled_network_workload():
+    """Config 3 at reduced N_m: gradients -> quantize/skip -> server step on the GPU,
+    teacher-forced against the oracle for a few iterations."""
+    w = laq_synth.workload(3, scale=0.02)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    ctx, st, theta = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta0)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    Gd = ctx.alloc_G()
+    msgs = ctx.alloc_messages()
+    for it in range(6):
+        ctx.laq_worker_grads(theta, Gd)
+        torch.cuda.synchronize()
+        G = Gd[:, :w.p].cpu().numpy()
+        G_ref, _ = oracle.grads_all(w.kind, st.theta, X, y, w.dims, w.lam)
+        err = np.abs(G - G_ref).max() / np.abs(G_ref).max()
+        assert err <= 1e-5, (it, err)
+        msgs, _ = check_quantize(ctx, st, Gd, G, msgs)
+        check_server(ctx, st, theta, msgs, G)
+        push_state(ctx, st)

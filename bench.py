@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""LAQ benchmark on one MI355X.
+
+A step is one LAQ iteration: laq_worker_grads -> laq_quantize_skip ->
+laq_server_step (Algorithm 2's loop body for all M workers), on synthetic
+inputs already resident in HBM.  The headline line is measured on the
+multinomial-logistic workload (M = 10 x 6000 samples, 785 x 10 parameters,
+b = 3); the other workloads of the study (network 784-200-10, the
+quantize/skip/aggregate bandwidth stress with M = 64 x 2^24 synthetic
+gradients, network 784-2048-2048-10 with M = 32 x 8192 samples) are timed in
+the same run and reported under "workloads" in the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--primary-only]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix
+
+
+def _events(torch, n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _roofline(bound, achieved, peak, unit, traffic=None, kernel=None, note=None):
+    d = {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+         "frac": round(achieved / peak, 4), "traffic": traffic}
+    if kernel:
+        d["kernel"] = kernel
+    if note:
+        d["note"] = note
+    return d
+
+
+def _traffic_table():
+    """Counter-measured HBM bytes per launch, written into profiles/ from rocprofv3 --pmc runs."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(path):
+        with open(path) as f:
+            return json.load(f)
+    return {}
+
+
+def run_model_workload(w, steps, warmup, phase_steps=100):
+    """Whole-loop rate and per-phase times of a model workload (cfg 1, 2, 3, 5)."""
+    import torch
+    import laq_synth
+    import paper_1909_07588_amd as laq
+    dev = "cuda:0"
+    X, y, theta0 = laq_synth.model_inputs(w)
+    ctx = laq.Laq(w.M, w.p, w.b, w.D, w.xi, w.t_bar, w.alpha, device=dev)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    Xd, yd = torch.from_numpy(X).to(dev), torch.from_numpy(y).to(dev)
+    ctx.laq_set_data(Xd, yd)
+    theta = torch.from_numpy(theta0.copy()).to(dev)
+    G = ctx.alloc_G()
+    codes, R, up = ctx.alloc_messages()
+
+    def step():
+        ctx.laq_worker_grads(theta, G)
+        ctx.laq_quantize_skip(G, codes, R, up)
+        ctx.laq_server_step(codes, R, up, theta)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch, 2)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    total_ms = e0.elapsed_time(e1)
+    uploads, bits, status = ctx.laq_get_counters()
+    assert status == 0, "non-finite radius during the benchmark"
+
+    # per-phase durations (separate, shorter loop with events between the calls)
+    n = max(1, min(phase_steps, steps))
+    ev = [_events(torch, 4) for _ in range(n)]
+    for i in range(n):
+        ev[i][0].record()
+        ctx.laq_worker_grads(theta, G)
+        ev[i][1].record()
+        ctx.laq_quantize_skip(G, codes, R, up)
+        ev[i][2].record()
+        ctx.laq_server_step(codes, R, up, theta)
+        ev[i][3].record()
+    torch.cuda.synchronize()
+    ph = [sum(e[k].elapsed_time(e[k + 1]) for e in ev) / n for k in range(3)]
+    it_total = warmup + steps
+    res = {
+        "workload": w.name, "M": w.M, "N_m": w.N_m, "p": w.p, "b": w.b, "steps": steps,
+        "iterations_per_s": round(steps / (total_ms * 1e-3), 2), "ms_per_step": round(total_ms / steps, 5),
+        "phase_ms": {"worker_grads": round(ph[0], 5), "quantize_skip": round(ph[1], 5),
+                     "server_step": round(ph[2], 5)},
+        "upload_fraction": round(float(uploads.sum()) / (w.M * it_total), 4),
+        "bits_total": int(bits),
+    }
+    ctx.close()
+    return res, ph
+
+
+def model_rooflines(w, ph, traffic):
+    """Rooflines of the three kernel groups of a model workload from their measured times."""
+    out = {}
+    elems = w.M * w.p
+    x_bytes = w.M * w.N_m * ((w.dims[0] + 3) // 4 * 4) * 4
+    if w.kind == 3:
+        S = w.M * w.N_m
+        d = w.dims
+        fwd = sum(2 * S * d[i] * d[i + 1] for i in range(len(d) - 1))
+        dA = sum(2 * S * d[i] * d[i + 1] for i in range(1, len(d) - 1))
+        flops = 2 * fwd + dA                      # forward + weight gradients + activation gradients
+        out["worker_grads"] = _roofline("mfma", flops / (ph[0] * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s",
+                                        traffic.get(w.name + ":worker_grads"), "gemm_kernel (fp32 MFMA) group")
+    else:
+        gb = (x_bytes + 4 * elems + 4 * w.p) / 1e9   # read X once, read theta, write G
+        out["worker_grads"] = _roofline("hbm", gb / (ph[0] * 1e-3), HBM_PEAK_GBS, "GB/s",
+                                        traffic.get(w.name + ":worker_grads"), "softmax_grad_kernel group")
+    gq = elems * (8 + w.b / 8) / 1e9
+    out["quantize_skip"] = _roofline("hbm", gq / (ph[1] * 1e-3), HBM_PEAK_GBS, "GB/s",
+                                     traffic.get(w.name + ":quantize_skip"), "radius_kernel + codes_kernel")
+    return out
+
+
+def run_stress(b, steps, warmup):
+    """Quantize/skip/aggregate bandwidth stress (synthetic gradients, no model)."""
+    import torch
+    import laq_synth
+    import paper_1909_07588_amd as laq
+    dev = "cuda:0"
+    w = laq_synth.workload(4)
+    M, p = w.M, w.p
+    ctx = laq.Laq(M, p, b, w.D, w.xi, w.t_bar, w.alpha, device=dev)
+    G, s, gen = laq_synth.device_gradients(M, p, ctx.p_stride, dev)
+    tmp = torch.empty_like(G[0])
+    theta = torch.zeros(p, dtype=torch.float32, device=dev)
+    codes, R, up = ctx.alloc_messages()
+    tq = ts = 0.0
+    n_up = 0
+    ups = []
+    for it in range(warmup + steps):
+        ev = _events(torch, 3)
+        ev[0].record()
+        ctx.laq_quantize_skip(G, codes, R, up)
+        ev[1].record()
+        ctx.laq_server_step(codes, R, up, theta)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if it >= warmup:
+            tq += ev[0].elapsed_time(ev[1])
+            ts += ev[1].elapsed_time(ev[2])
+            ups.append(int(up.sum().item()))
+        laq_synth.device_drift_(G, s, gen, tmp)     # next iteration's gradients (not timed)
+    torch.cuda.synchronize()
+    tq /= steps
+    ts /= steps
+    n_up = sum(ups)
+    elems = M * p
+    alg_q = elems * (8 + b / 8) / 1e9
+    alg_s = (n_up / steps) * p * (8 + b / 8) / 1e9 + 16 * p / 1e9
+    res = {
+        "workload": f"{w.name}_b{b}", "M": M, "p": p, "b": b, "steps": steps,
+        "iterations_per_s": round(1e3 / (tq + ts), 2), "ms_per_step": round(tq + ts, 4),
+        "phase_ms": {"quantize_skip": round(tq, 4), "server_step": round(ts, 4)},
+        "upload_fraction": round(n_up / (steps * M), 4),
+        "quantized_gradient_GBps": round(elems * 4 / 1e9 / (tq * 1e-3), 1),
+    }
+    ctx.close()
+    return res, (alg_q, tq, alg_s, ts)
+
+
+def cpu_baseline(w, budget_s=12.0, max_iters=50):
+    """The oracle, as it stands, on the host cores: whole LAQ iterations of the same workload."""
+    import numpy as np
+    import laq_synth
+    import oracle
+    X, y, theta0 = laq_synth.model_inputs(w)
+    st = oracle.State(w.M, w.p, w.b, w.D, w.xi, w.t_bar, w.alpha, theta0)
+    oracle.lib()
+    t0 = time.perf_counter()
+    n = 0
+    while n < max_iters and (time.perf_counter() - t0) < budget_s:
+        G, _ = oracle.grads_all(w.kind, st.theta, X, y, w.dims, w.lam)
+        out = st.iteration(G, want_codes=False)
+        assert out["status"] == 0
+        n += 1
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    used = min(threads, w.M) if w.kind != 3 else threads
+    return {"value": round(n / dt, 4), "unit": "iterations/s", "cores": used, "kind": "oracle",
+            "sample": f"first {n} iterations of {w.name} (full size, all {w.M} workers), "
+                      f"gcc -O2 -ffp-contract=off, OpenMP over workers"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--primary-only", action="store_true", help="skip the other workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 5], help="headline workload")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all M workers are simulated on one MI355X); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import laq_synth
+    import paper_1909_07588_amd as laq
+    laq.lib()                                   # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    traffic = _traffic_table()
+
+    w = laq_synth.workload(args.workload)
+    res, ph = run_model_workload(w, args.steps, args.warmup)
+    roofs = model_rooflines(w, ph, traffic)
+    dominant = max(("worker_grads", "quantize_skip"), key=lambda k: res["phase_ms"][k])
+    workloads = [dict(res, rooflines=roofs)]
+
+    if not args.primary_only:
+        for cfg, k, wu in ((3, 200, 10), (5, 6, 2)):
+            if cfg == args.workload:
+                continue
+            wk = laq_synth.workload(cfg)
+            r, p3 = run_model_workload(wk, k, wu, phase_steps=min(k, 50))
+            workloads.append(dict(r, rooflines=model_rooflines(wk, p3, traffic)))
+            torch.cuda.empty_cache()
+        for b in (2, 4, 8):
+            r, (alg_q, tq, alg_s, ts) = run_stress(b, 50, 3)
+            name = r["workload"]
+            r["rooflines"] = {
+                "quantize_skip": _roofline("hbm", alg_q / (tq * 1e-3), HBM_PEAK_GBS, "GB/s",
+                                           traffic.get(name + ":quantize_skip"), "radius_kernel + codes_kernel",
+                                           "algorithmic bytes 8 + b/8 per worker-element; the radius needs a "
+                                           "first full read of g and h, so HBM traffic is about twice that"),
+                "server_step": _roofline("hbm", alg_s / (ts * 1e-3), HBM_PEAK_GBS, "GB/s",
+                                         traffic.get(name + ":server_step"), "server_kernel"),
+            }
+            workloads.append(r)
+            torch.cuda.empty_cache()
+
+    line = {
+        "metric": "LAQ iterations/sec and worker-gradient GB/s quantized (fraction of HBM peak)",
+        "value": res["iterations_per_s"], "unit": "iterations/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "N_m": w.N_m, "p": w.p, "b": w.b, "D": w.D,
+                   "xi": w.xi, "t_bar": w.t_bar, "alpha": w.alpha, "lambda": w.lam},
+        "roofline": roofs[dominant],
+        "workloads": workloads,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,164 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
   }
 }
 
+// ------------------------------------------------------------------ multinomial logistic regression on the matrix cores
+//
+// Both products of the softmax-regression gradient are skinny GEMMs:
+//   Z[16 rows][C] = X[16][F] Theta^T        and        Gacc[C][F] += R^T[C][16] X[16][F].
+// They map onto v_mfma_f32_16x16x4_f32 with the class dimension padded to 16.
+// One block (4 wavefronts) owns a range of rows and walks it in tiles of 16
+// rows: the tile is copied once from HBM to LDS (contiguous, coalesced,
+// prefetched into registers one tile ahead); for the logits the 4 waves split
+// the feature dimension and their partial products are summed through LDS;
+// after the softmax the 4 waves split the feature tiles of the rank-16 update
+// and keep their part of Gacc in registers for the whole row range.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int kRT = 16;   // rows per tile
+
+template <int TMAX>
+__global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
+    const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
+    int64_t N_m, int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, int32_t ldsF,
+    float* __restrict__ part) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* Th = smem;                          // [C][ldsF], columns >= F are zero
+  float* Xs0 = Th + (int64_t)C * ldsF;       // [16][ldsF]
+  float* Xs1 = Xs0 + kRT * ldsF;
+  float* Zp = Xs1 + kRT * ldsF;              // [4][16][16] partial logits
+  float* Rs = Zp + 4 * 256;                  // [16][16] residuals P - Y
+
+  const int m = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lq = lane >> 4;
+  const float* Xm = X + (int64_t)m * N_m * ldx;
+  const int32_t* ym = y + (int64_t)m * N_m;
+  const int nchunk = (F + 15) / 16, FP = nchunk * 16, nf4 = FP / 4;
+
+  for (int idx = tid; idx < C * FP; idx += kThreads) {
+    const int c = idx / FP, f = idx - c * FP;
+    Th[c * ldsF + f] = f < F ? theta[(int64_t)c * F + f] : 0.0f;
+  }
+
+  const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+  int64_t r_end = r_begin + rows_per_block;
+  if (r_end > N_m) r_end = N_m;
+
+  constexpr int PF = (kRT * 4 * TMAX * 16 / 4 + kThreads - 1) / kThreads;   // float4 per lane per tile
+  float4 pre[PF];
+  auto gload = [&](int64_t r0) {
+#pragma unroll
+    for (int q = 0; q < PF; ++q) {
+      const int idx = tid + kThreads * q;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (idx < kRT * nf4) {
+        const int row = idx / nf4, f = (idx - row * nf4) * 4;
+        const int64_t gr = r0 + row;
+        if (gr < r_end && f < F) {
+          const float* src = Xm + gr * ldx + f;
+          if (f + 3 < F) {
+            v = *reinterpret_cast<const float4*>(src);
+          } else {
+            v.x = src[0];
+            if (f + 1 < F) v.y = src[1];
+            if (f + 2 < F) v.z = src[2];
+          }
+        }
+      }
+      pre[q] = v;
+    }
+  };
+  auto lstore = [&](float* buf) {
+#pragma unroll
+    for (int q = 0; q < PF; ++q) {
+      const int idx = tid + kThreads * q;
+      if (idx < kRT * nf4) {
+        const int row = idx / nf4, f = (idx - row * nf4) * 4;
+        *reinterpret_cast<float4*>(&buf[row * ldsF + f]) = pre[q];
+      }
+    }
+  };
+
+  floatx4 acc2[TMAX];
+#pragma unroll
+  for (int n = 0; n < TMAX; ++n) acc2[n] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  gload(r_begin);
+  lstore(Xs0);
+  __syncthreads();
+  int cur = 0;
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
+    float* Xs = cur ? Xs1 : Xs0;
+    const bool more = r0 + kRT < r_end;
+    if (more) gload(r0 + kRT);
+
+    // logits: wave w multiplies feature chunks t = w, w+4, ...
+    floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = wave; t < nchunk; t += 4) {
+      const float4 a = *reinterpret_cast<const float4*>(&Xs[l16 * ldsF + 16 * t + 4 * lq]);
+      float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (l16 < C) b = *reinterpret_cast<const float4*>(&Th[l16 * ldsF + 16 * t + 4 * lq]);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) Zp[wave * 256 + (4 * lq + r) * 16 + l16] = acc1[r];
+    __syncthreads();
+
+    // softmax and residual: thread (i = tid/16, j = tid%16)
+    {
+      const int i = tid >> 4, j = tid & 15;
+      const float z = (Zp[tid] + Zp[256 + tid]) + (Zp[512 + tid] + Zp[768 + tid]);
+      const bool valid = j < C;
+      float zm = valid ? z : -INFINITY;
+#pragma unroll
+      for (int off = 8; off > 0; off >>= 1) zm = fmaxf(zm, __shfl_xor(zm, off));
+      const float e = valid ? expf(z - zm) : 0.0f;
+      float den = e;
+#pragma unroll
+      for (int off = 8; off > 0; off >>= 1) den += __shfl_xor(den, off);
+      const int64_t gr = r0 + i;
+      float rv = 0.0f;
+      if (valid && gr < r_end) rv = e / den - (j == ym[gr] ? 1.0f : 0.0f);
+      Rs[tid] = rv;
+    }
+    __syncthreads();
+
+    // rank-16 update: wave w owns feature tiles ft = w, w+4, ...
+    float ar[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) ar[u] = Rs[(4 * u + lq) * 16 + l16];
+#pragma unroll
+    for (int n = 0; n < TMAX; ++n) {
+      const int ft = wave + 4 * n;
+      if (ft < nchunk) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float b = Xs[(4 * u + lq) * ldsF + 16 * ft + l16];
+          acc2[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[u], b, acc2[n], 0, 0, 0);
+        }
+      }
+    }
+    if (more) lstore(cur ? Xs0 : Xs1);
+    __syncthreads();
+    cur ^= 1;
+  }
+
+  float* out = part + ((int64_t)m * gridDim.x + blockIdx.x) * ((int64_t)C * F);
+#pragma unroll
+  for (int n = 0; n < TMAX; ++n) {
+    const int f = 16 * (wave + 4 * n) + l16;
+    if (f < F) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int c = 4 * lq + r;
+        if (c < C) out[(int64_t)c * F + f] = acc2[n][r];
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ binary logistic
 //
 // l = log(1 + exp(-y x.theta)), y in {-1,+1}; dl/dtheta = -y x / (1 + exp(y x.theta)).
@@ -199,7 +357,30 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
 
 // ------------------------------------------------------------------ host side
 
+// LDS layout of the matrix-core softmax kernel: row stride (floats) and bytes; 0 if it does not fit.
+static size_t softmax_mfma_lds(const laq_ctx* ctx, int* ldsF_out) {
+  if (ctx->kind != LAQ_MODEL_SOFTMAX || ctx->C > 16) return 0;
+  const int FP = (ctx->F + 15) / 16 * 16;
+  if (FP > 16 * 4 * 14) return 0;
+  const int pad = (20 - FP % 32 + 32) % 32;       // row stride = 20 (mod 32) banks: conflict-free b128 reads
+  const int ldsF = FP + pad;
+  const size_t bytes = ((size_t)(ctx->C + 2 * kRT) * ldsF + 5 * 256) * sizeof(float);
+  if (bytes > 150 * 1024) return 0;
+  if (ldsF_out) *ldsF_out = ldsF;
+  return bytes;
+}
+
 static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block) {
+  if (softmax_mfma_lds(ctx, nullptr)) {
+    // one block per CU at most (LDS-bound occupancy), whole tiles of 16 rows per block
+    int64_t want = ctx->n_cu / ctx->M;
+    if (want < 1) want = 1;
+    const int64_t tiles = (N_m + kRT - 1) / kRT;
+    if (want > tiles) want = tiles;
+    const int64_t tpb = (tiles + want - 1) / want;
+    *rows_per_block = (int)(tpb * kRT);
+    return (int)((tiles + tpb - 1) / tpb);
+  }
   // about two blocks per CU over all workers, at least 4 rows per wave
   int64_t want = ((int64_t)ctx->n_cu * 2 + ctx->M - 1) / ctx->M;
   int64_t max_by_rows = (N_m + 15) / 16;
@@ -249,7 +430,23 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   float* part = reinterpret_cast<float*>(ctx->model_ws);
   const dim3 grid((unsigned)nb, (unsigned)ctx->M);
   const int kf = (ctx->F + 63) / 64;
-  if (ctx->kind == LAQ_MODEL_SOFTMAX) {
+  int ldsF = 0;
+  const size_t mfma_lds = softmax_mfma_lds(ctx, &ldsF);
+  if (mfma_lds) {
+    const int nchunk = (ctx->F + 15) / 16;
+#define LAQ_SMM(T)                                                                                     \
+  do {                                                                                                 \
+    LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_grad_mfma_kernel<T>),       \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
+    hipLaunchKernelGGL((softmax_grad_mfma_kernel<T>), grid, dim3(kThreads), mfma_lds, ctx->stream,      \
+                       theta, ctx->X, ctx->y, ctx->N_m, ctx->ldx, ctx->F, ctx->C, rpb, ldsF, part);     \
+  } while (0)
+    if (nchunk <= 4) LAQ_SMM(1);
+    else if (nchunk <= 16) LAQ_SMM(4);
+    else if (nchunk <= 32) LAQ_SMM(8);
+    else LAQ_SMM(14);
+#undef LAQ_SMM
+  } else if (ctx->kind == LAQ_MODEL_SOFTMAX) {
     if (kf <= 1) launch_softmax<1>(ctx, grid, theta, rpb, part);
     else if (kf <= 2) launch_softmax<2>(ctx, grid, theta, rpb, part);
     else if (kf <= 4) launch_softmax<4>(ctx, grid, theta, rpb, part);

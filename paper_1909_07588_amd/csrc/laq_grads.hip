@@ -133,15 +133,16 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
 // They map onto v_mfma_f32_16x16x4_f32 with the class dimension padded to 16.
 // One block (4 wavefronts) owns a range of rows and walks it in tiles of 16
 // rows: the tile is copied once from HBM to LDS (contiguous, coalesced,
-// prefetched into registers one tile ahead); for the logits the 4 waves split
+// prefetched into registers one tile ahead); for the logits the NW waves split
 // the feature dimension and their partial products are summed through LDS;
-// after the softmax the 4 waves split the feature tiles of the rank-16 update
-// and keep their part of Gacc in registers for the whole row range.
+// after the softmax the waves split the feature tiles of the rank-16 update
+// and keep their part of Gacc in registers for the whole row range.  LDS holds
+// one block per CU, so the block is wide (16 waves) to keep 4 waves per SIMD.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kRT = 16;   // rows per tile
 
-template <int TMAX>
-__global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
+template <int NW, int TMAX>
+__global__ __launch_bounds__(64 * NW) void softmax_grad_mfma_kernel(
     const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
     int64_t N_m, int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, int32_t ldsF,
     float* __restrict__ part) {
@@ -149,8 +150,9 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
   float* Th = smem;                          // [C][ldsF], columns >= F are zero
   float* Xs0 = Th + (int64_t)C * ldsF;       // [16][ldsF]
   float* Xs1 = Xs0 + kRT * ldsF;
-  float* Zp = Xs1 + kRT * ldsF;              // [4][16][16] partial logits
-  float* Rs = Zp + 4 * 256;                  // [16][16] residuals P - Y
+  float* Zp = Xs1 + kRT * ldsF;              // [NW][16][16] partial logits
+  float* Rs = Zp + NW * 256;                 // [16][16] residuals P - Y
+  int* Ys = reinterpret_cast<int*>(Rs + 256);  // [2][16] labels of the current / next tile
 
   const int m = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -159,7 +161,8 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
   const int32_t* ym = y + (int64_t)m * N_m;
   const int nchunk = (F + 15) / 16, FP = nchunk * 16, nf4 = FP / 4;
 
-  for (int idx = tid; idx < C * FP; idx += kThreads) {
+  constexpr int NT = 64 * NW;
+  for (int idx = tid; idx < C * FP; idx += NT) {
     const int c = idx / FP, f = idx - c * FP;
     Th[c * ldsF + f] = f < F ? theta[(int64_t)c * F + f] : 0.0f;
   }
@@ -168,37 +171,44 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
   int64_t r_end = r_begin + rows_per_block;
   if (r_end > N_m) r_end = N_m;
 
-  constexpr int PF = (kRT * 4 * TMAX * 16 / 4 + kThreads - 1) / kThreads;   // float4 per lane per tile
+  constexpr int PF = (kRT * NW * TMAX * 16 / 4 + NT - 1) / NT;   // float4 per lane per tile
+  // Tile prefetch: every lane issues PF unconditional 16-byte loads (row and
+  // column indices clamped into the matrix; rows are padded to ldx, a multiple
+  // of 4, so a float4 that starts below F stays inside its row) and the
+  // masking of rows >= r_end and columns >= F happens when the registers are
+  // written to LDS.  No branch and no wait sits between the loads and the
+  // matrix work they overlap with.
   float4 pre[PF];
+  int ypre = 0;
+  const int64_t last_row = r_end - 1;
   auto gload = [&](int64_t r0) {
+    if (tid < kRT) ypre = ym[(r0 + tid < r_end) ? r0 + tid : last_row];
 #pragma unroll
     for (int q = 0; q < PF; ++q) {
-      const int idx = tid + kThreads * q;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (idx < kRT * nf4) {
-        const int row = idx / nf4, f = (idx - row * nf4) * 4;
-        const int64_t gr = r0 + row;
-        if (gr < r_end && f < F) {
-          const float* src = Xm + gr * ldx + f;
-          if (f + 3 < F) {
-            v = *reinterpret_cast<const float4*>(src);
-          } else {
-            v.x = src[0];
-            if (f + 1 < F) v.y = src[1];
-            if (f + 2 < F) v.z = src[2];
-          }
-        }
-      }
-      pre[q] = v;
+      int idx = tid + NT * q;
+      idx = idx < kRT * nf4 ? idx : kRT * nf4 - 1;
+      const int row = idx / nf4;
+      int f = (idx - row * nf4) * 4;
+      f = f < F ? f : 0;
+      int64_t gr = r0 + row;
+      gr = gr < r_end ? gr : last_row;
+      pre[q] = *reinterpret_cast<const float4*>(Xm + gr * ldx + f);
     }
   };
-  auto lstore = [&](float* buf) {
+  auto lstore = [&](float* buf, int which, int64_t r0) {
+    if (tid < kRT) Ys[which * kRT + tid] = ypre;
 #pragma unroll
     for (int q = 0; q < PF; ++q) {
-      const int idx = tid + kThreads * q;
+      const int idx = tid + NT * q;
       if (idx < kRT * nf4) {
         const int row = idx / nf4, f = (idx - row * nf4) * 4;
-        *reinterpret_cast<float4*>(&buf[row * ldsF + f]) = pre[q];
+        const bool rv = r0 + row < r_end;
+        float4 v = pre[q];
+        v.x = (rv && f < F) ? v.x : 0.0f;
+        v.y = (rv && f + 1 < F) ? v.y : 0.0f;
+        v.z = (rv && f + 2 < F) ? v.z : 0.0f;
+        v.w = (rv && f + 3 < F) ? v.w : 0.0f;
+        *reinterpret_cast<float4*>(&buf[row * ldsF + f]) = v;
       }
     }
   };
@@ -208,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
   for (int n = 0; n < TMAX; ++n) acc2[n] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   gload(r_begin);
-  lstore(Xs0);
+  lstore(Xs0, 0, r_begin);
   __syncthreads();
   int cur = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
@@ -216,9 +226,9 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
     const bool more = r0 + kRT < r_end;
     if (more) gload(r0 + kRT);
 
-    // logits: wave w multiplies feature chunks t = w, w+4, ...
+    // logits: wave w multiplies feature chunks t = w, w+NW, ...
     floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-    for (int t = wave; t < nchunk; t += 4) {
+    for (int t = wave; t < nchunk; t += NW) {
       const float4 a = *reinterpret_cast<const float4*>(&Xs[l16 * ldsF + 16 * t + 4 * lq]);
       float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
       if (l16 < C) b = *reinterpret_cast<const float4*>(&Th[l16 * ldsF + 16 * t + 4 * lq]);
@@ -232,9 +242,11 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
     __syncthreads();
 
     // softmax and residual: thread (i = tid/16, j = tid%16)
-    {
+    if (tid < 256) {
       const int i = tid >> 4, j = tid & 15;
-      const float z = (Zp[tid] + Zp[256 + tid]) + (Zp[512 + tid] + Zp[768 + tid]);
+      float z = Zp[tid];
+#pragma unroll
+      for (int wv = 1; wv < NW; ++wv) z += Zp[wv * 256 + tid];
       const bool valid = j < C;
       float zm = valid ? z : -INFINITY;
 #pragma unroll
@@ -245,18 +257,18 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
       for (int off = 8; off > 0; off >>= 1) den += __shfl_xor(den, off);
       const int64_t gr = r0 + i;
       float rv = 0.0f;
-      if (valid && gr < r_end) rv = e / den - (j == ym[gr] ? 1.0f : 0.0f);
+      if (valid && gr < r_end) rv = e / den - (j == Ys[cur * kRT + i] ? 1.0f : 0.0f);
       Rs[tid] = rv;
     }
     __syncthreads();
 
-    // rank-16 update: wave w owns feature tiles ft = w, w+4, ...
+    // rank-16 update: wave w owns feature tiles ft = w, w+NW, ...
     float ar[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) ar[u] = Rs[(4 * u + lq) * 16 + l16];
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
-      const int ft = wave + 4 * n;
+      const int ft = wave + NW * n;
       if (ft < nchunk) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -265,7 +277,7 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
         }
       }
     }
-    if (more) lstore(cur ? Xs0 : Xs1);
+    if (more) lstore(cur ? Xs0 : Xs1, cur ^ 1, r0 + kRT);
     __syncthreads();
     cur ^= 1;
   }
@@ -273,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_mfma_kernel(
   float* out = part + ((int64_t)m * gridDim.x + blockIdx.x) * ((int64_t)C * F);
 #pragma unroll
   for (int n = 0; n < TMAX; ++n) {
-    const int f = 16 * (wave + 4 * n) + l16;
+    const int f = 16 * (wave + NW * n) + l16;
     if (f < F) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -357,15 +369,17 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
 
 // ------------------------------------------------------------------ host side
 
+constexpr int kSmxWaves = 16;
+
 // LDS layout of the matrix-core softmax kernel: row stride (floats) and bytes; 0 if it does not fit.
 static size_t softmax_mfma_lds(const laq_ctx* ctx, int* ldsF_out) {
   if (ctx->kind != LAQ_MODEL_SOFTMAX || ctx->C > 16) return 0;
   const int FP = (ctx->F + 15) / 16 * 16;
-  if (FP > 16 * 4 * 14) return 0;
+  if (FP > 16 * kSmxWaves * 4) return 0;
   const int pad = (20 - FP % 32 + 32) % 32;       // row stride = 20 (mod 32) banks: conflict-free b128 reads
   const int ldsF = FP + pad;
-  const size_t bytes = ((size_t)(ctx->C + 2 * kRT) * ldsF + 5 * 256) * sizeof(float);
-  if (bytes > 150 * 1024) return 0;
+  const size_t bytes = ((size_t)(ctx->C + 2 * kRT) * ldsF + (kSmxWaves + 1) * 256 + 2 * kRT) * sizeof(float);
+  if (bytes > 160 * 1024) return 0;
   if (ldsF_out) *ldsF_out = ldsF;
   return bytes;
 }
@@ -436,15 +450,15 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     const int nchunk = (ctx->F + 15) / 16;
 #define LAQ_SMM(T)                                                                                     \
   do {                                                                                                 \
-    LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_grad_mfma_kernel<T>),       \
+    auto kfn = softmax_grad_mfma_kernel<kSmxWaves, T>;                                                 \
+    LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                               \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
-    hipLaunchKernelGGL((softmax_grad_mfma_kernel<T>), grid, dim3(kThreads), mfma_lds, ctx->stream,      \
-                       theta, ctx->X, ctx->y, ctx->N_m, ctx->ldx, ctx->F, ctx->C, rpb, ldsF, part);     \
+    hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta, ctx->X, ctx->y,   \
+                       ctx->N_m, ctx->ldx, ctx->F, ctx->C, rpb, ldsF, part);                            \
   } while (0)
-    if (nchunk <= 4) LAQ_SMM(1);
-    else if (nchunk <= 16) LAQ_SMM(4);
-    else if (nchunk <= 32) LAQ_SMM(8);
-    else LAQ_SMM(14);
+    if (nchunk <= kSmxWaves) LAQ_SMM(1);
+    else if (nchunk <= 2 * kSmxWaves) LAQ_SMM(2);
+    else LAQ_SMM(4);
 #undef LAQ_SMM
   } else if (ctx->kind == LAQ_MODEL_SOFTMAX) {
     if (kf <= 1) launch_softmax<1>(ctx, grid, theta, rpb, part);

@@ -177,6 +177,36 @@ def run_stress(b, steps, warmup):
     return res, (alg_q, tq, alg_s, ts)
 
 
+def pmc_probe():
+    """Short fixed sequence for counter collection under `rocprofv3 --pmc`: a 1 GiB device
+    copy (calibrates FETCH_SIZE / WRITE_SIZE against a known size), three iterations of the
+    bandwidth-stress workload at b = 4, twenty iterations of the headline workload."""
+    import torch
+    import laq_synth
+    import paper_1909_07588_amd as laq
+    dev = "cuda:0"
+    a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    c = torch.empty_like(a)
+    for _ in range(3):
+        c.copy_(a)
+    torch.cuda.synchronize()
+    del a, c
+    w = laq_synth.workload(4)
+    ctx = laq.Laq(w.M, w.p, 4, w.D, w.xi, w.t_bar, w.alpha, device=dev)
+    G, s, gen = laq_synth.device_gradients(w.M, w.p, ctx.p_stride, dev)
+    theta = torch.zeros(w.p, dtype=torch.float32, device=dev)
+    codes, R, up = ctx.alloc_messages()
+    for _ in range(3):
+        ctx.laq_quantize_skip(G, codes, R, up)
+        ctx.laq_server_step(codes, R, up, theta)
+        laq_synth.device_drift_(G, s, gen)
+    torch.cuda.synchronize()
+    ctx.close()
+    del G
+    run_model_workload(laq_synth.workload(2), 20, 2, phase_steps=1)
+    print("pmc probe done", flush=True)
+
+
 def cpu_baseline(w, budget_s=12.0, max_iters=50):
     """The oracle, as it stands, on the host cores: whole LAQ iterations of the same workload."""
     import numpy as np
@@ -208,6 +238,7 @@ def main():
     ap.add_argument("--primary-only", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 5], help="headline workload")
+    ap.add_argument("--pmc-probe", action="store_true", help="short run for rocprofv3 --pmc (no timing)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all M workers are simulated on one MI355X); "
@@ -221,6 +252,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.pmc_probe:
+        pmc_probe()
+        return
     traffic = _traffic_table()
 
     w = laq_synth.workload(args.workload)

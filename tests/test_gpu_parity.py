@@ -288,3 +288,57 @@ def test_full_loop_on_a_scaled_network_workload():
         msgs, _ = check_quantize(ctx, st, Gd, G, msgs)
         check_server(ctx, st, theta, msgs, G)
         push_state(ctx, st)
+
+
+def test_full_size_stress_shape_all_workers():
+    """The bandwidth-stress workload at its full size (M = 64, p = 2^24, b = 4), in the launch
+    configuration bench.py times: radii, both integer sums, both sides of (7a) and the masks
+    of all 64 workers, the packed codes of 6 sampled workers, and one whole server step."""
+    w = laq_synth.workload(4)
+    M, p, b = w.M, w.p, 4
+    ctx, st, theta = make_pair(M, p, b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha)
+    Gd, s, gen = laq_synth.device_gradients(M, p, ctx.p_stride, DEV)
+    codes, R, up = ctx.alloc_messages()
+    for it in range(2):
+        G = Gd[:, :p].cpu().numpy()
+        ctx.laq_quantize_skip(Gd, codes, R, up)
+        torch.cuda.synchronize()
+        sview = ctx.state()
+        R_h, up_h = R.cpu().numpy(), up.cpu().numpy()
+        Sq_h, E2_h = sview["Sq"].cpu().numpy(), sview["E2"].cpu().numpy()
+        lhs_h, rhs_h = sview["lhs"].cpu().numpy(), sview["rhs"].cpu().numpy()
+        nw = oracle.code_words(p, b)
+        sampled = {0, 7, 21, 40, 62, 63}
+        for m in range(M):
+            o = oracle.quantize(G[m], st.H[m], b, want_vectors=(m in sampled))
+            skip, rhs = oracle.skip(o["lhs"], o["E2"], st.Ehat2[m], st.xi, st.dtheta2, st.alpha, M,
+                                    st.t[m], st.t_bar)
+            assert bits_equal(np.float32(R_h[m]), np.float32(o["R"])), m
+            assert int(Sq_h[m]) == o["Sq"] and bits_equal(np.float64(E2_h[m]), np.float64(o["E2"])), m
+            assert bits_equal(np.float64(lhs_h[m]), np.float64(o["lhs"])), m
+            assert bits_equal(np.float64(rhs_h[m]), np.float64(rhs)), m
+            assert int(up_h[m]) == int(not skip), m
+            if m in sampled:
+                got = codes[m, :nw].cpu().numpy().view(np.uint32)
+                assert np.array_equal(got, oracle.pack(o["q"], b)), m
+        out = st.iteration(G, want_codes=False)
+        ctx.laq_server_step(codes, R, up, theta)
+        torch.cuda.synchronize()
+        assert np.array_equal(up_h, out["upload"])
+        assert bits_equal(theta.cpu().numpy(), st.theta)
+        assert bits_equal(sview["nabla"][:p].cpu().numpy(), st.nabla)
+        for m in (0, 21, 63):
+            assert bits_equal(sview["H"][m, :p].cpu().numpy(), st.H[m]), m
+        assert np.allclose(sview["dtheta2"].cpu().numpy(), st.dtheta2, rtol=4.0 * p * 2.0 ** -53, atol=0)
+        push_state(ctx, st)
+        laq_synth.device_drift_(Gd, s, gen)
+
+
+def test_largest_network_widths_at_reduced_batch():
+    """The 784-2048-2048-10 network of the largest workload (full layer widths, so the GEMM
+    tiling and the class-layer kernels run at their real shapes) with fewer samples per worker."""
+    dims = (784, 2048, 2048, 10)
+    w = laq_synth.Workload("t", 5, laq_synth.KIND_MLP, 2, 192, dims, laq_synth.mlp_param_count(dims), 4)
+    G, G_ref = _grad_case(w)
+    err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
+    assert err.max() <= 1e-5, err

@@ -131,6 +131,9 @@ int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t
  * Algorithm 2, worker step, first half: G_dev[m][0..p) = grad f_m(theta) for
  * all M workers (fp32 arithmetic; row stride laq_p_stride(p)).
  * theta_dev[p] is read only.  Needs laq_set_model and laq_set_data.
+ * The kernels that write G also leave max |g - h| per block, so a following
+ * laq_quantize_skip on the same G_dev, with the state untouched in between,
+ * skips its radius pass (one read of G and of the stored gradients less).
  */
 int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev);
 
@@ -170,7 +173,10 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
 
 /* Device pointers into the workspace (valid until laq_destroy).  The caller
  * may read or overwrite them between calls with stream-ordered copies; this
- * is how a checkpoint is saved, restored, or a reference state is imposed. */
+ * is how a checkpoint is saved, restored, or a reference state is imposed.
+ * Call laq_get_state again before each round of writes: the call also drops
+ * the radius that laq_worker_grads may have handed to laq_quantize_skip (it
+ * was computed against the stored gradients as they were). */
 typedef struct laq_state_view {
   float* H_dev;            /* [M][p_stride] stored Q_m(theta_hat_m)            */
   float* nabla_dev;        /* [p_stride]                                       */

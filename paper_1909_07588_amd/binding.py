@@ -147,8 +147,13 @@ class Laq:
         return self.ws[off:off + nbytes].view(dtype)
 
     def state(self):
-        """Views (not copies) of the state held in the workspace."""
-        torch, v = self.torch, self._view
+        """Views (not copies) of the state held in the workspace.  Goes through
+        laq_get_state every time: the call tells the library that the state may
+        be overwritten, so a radius handed over by laq_worker_grads is dropped."""
+        v = StateView()
+        self._chk(self.L.laq_get_state(self.h, C.byref(v)))
+        self._view = v
+        torch = self.torch
         M, D = self.M, self.D
         return dict(
             H=self._ws_tensor(v.H_dev, M * self.p_stride, torch.float32).view(M, self.p_stride),

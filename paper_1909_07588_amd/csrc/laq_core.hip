@@ -148,17 +148,18 @@ __global__ __launch_bounds__(kThreads) void radius_kernel(const float* __restric
   }
 }
 
-// R_m from the block partials of the first pass.
-__global__ __launch_bounds__(kThreads) void radius_final_kernel(int32_t n_slots, int32_t slots,
-                                                                DeviceScalars sc) {
+// R_m from block partials src[m][0..count) (first pass, or a gradient kernel's epilogue).
+__global__ __launch_bounds__(kThreads) void radius_final_kernel(const uint32_t* __restrict__ src,
+                                                                int32_t stride, int32_t count,
+                                                                uint32_t* __restrict__ Rfin) {
   __shared__ uint32_t sm[kThreads / 64];
   const int m = blockIdx.x;
   uint32_t mx = 0;
-  for (int i = threadIdx.x; i < n_slots; i += kThreads) mx = max(mx, sc.Rpart[(int64_t)m * slots + i]);
+  for (int i = threadIdx.x; i < count; i += kThreads) mx = max(mx, src[(int64_t)m * stride + i]);
   mx = wave_max_u32(mx);
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
   __syncthreads();
-  if (threadIdx.x == 0) sc.Rfin[m] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
+  if (threadIdx.x == 0) Rfin[m] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
 // ------------------------------------------------------------------ pass 2: codes + skip rule
@@ -171,7 +172,11 @@ struct QuantArgs {
   uint8_t* upload;
   DeviceScalars sc;
   int64_t p, p_stride, w_stride;
-  int32_t M, D, t_bar, eps_K, slots, fused_radius, U;
+  int32_t M, D, t_bar, eps_K, slots, U;
+  // radius source: either the finished value Rfin[m] (rcount == 0) or at most 64
+  // block maxima rsrc[m * rstride + i], i < rcount, combined on the fly
+  const uint32_t* rsrc;
+  int32_t rstride, rcount;
   float alpha;
   uint32_t mode;
 };
@@ -250,10 +255,9 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     const float* h = a.H + (int64_t)m * a.p_stride;
     uint8_t* out = reinterpret_cast<uint8_t*>(a.codes + (int64_t)m * a.w_stride);
     uint32_t rbits;
-    if (a.fused_radius) {
-      // at most 64 slots: combine the first pass's maxima here (one launch less)
+    if (a.rcount > 0) {
       const int lane = threadIdx.x & 63;
-      rbits = lane < (int)gridDim.x ? a.sc.Rpart[(int64_t)m * a.slots + lane] : 0u;
+      rbits = lane < a.rcount ? a.rsrc[(int64_t)m * a.rstride + lane] : 0u;
       rbits = wave_max_u32(rbits);
     } else {
       rbits = a.sc.Rfin[m];
@@ -322,7 +326,11 @@ __global__ __launch_bounds__(kThreads) void decide_kernel(QuantArgs a, int32_t n
   for (int i = threadIdx.x; i < n_slots; i += kThreads) {
     s64 += a.sc.Spart[(int64_t)m * a.slots + i];
     n64 += a.sc.Npart[(int64_t)m * a.slots + i];
-    rb = max(rb, a.sc.Rpart[(int64_t)m * a.slots + i]);
+  }
+  if (a.rcount > 0) {
+    if ((int)threadIdx.x < a.rcount) rb = a.rsrc[(int64_t)m * a.rstride + threadIdx.x];
+  } else if (threadIdx.x == 0) {
+    rb = a.sc.Rfin[m];
   }
   s64 = wave_sum_u64(s64);
   n64 = wave_sum_u64(n64);
@@ -663,6 +671,7 @@ size_t laq_workspace_bytes(int32_t M, int64_t p, int32_t b, int32_t D) {
 
 int laq_reset(laq_ctx* ctx) {
   if (!ctx) return LAQ_EINVAL;
+  ctx->radius_for = nullptr;
   const Layout l = make_layout(ctx->M, ctx->p, ctx->D);
   // H, nabla and every scalar except xi start at zero; clocks start at t_bar
   LAQ_HIP(ctx, hipMemsetAsync(ctx->ws, 0, l.xi, ctx->stream));
@@ -766,12 +775,20 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   const Sweep sw = make_sweep(ctx->p, ctx->M);
   const dim3 grid((unsigned)sw.Gx, (unsigned)ctx->M);
   a.U = sw.U;
-  hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
-                     ctx->p_stride, sw.U, a.slots, ctx->sc);
-  a.fused_radius = sw.Gx <= 64;
-  if (!a.fused_radius)
-    hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
-                       sw.Gx, a.slots, ctx->sc);
+  if (ctx->radius_for == G_dev && G_dev != nullptr) {
+    // laq_worker_grads produced these gradients and left the block maxima of
+    // |g - h| behind: the radius pass (a full read of g and h) is not needed
+    a.rsrc = ctx->rprod; a.rstride = ctx->rprod_stride;
+    a.rcount = ctx->rprod_count <= 64 ? ctx->rprod_count : 0;   // > 64: Rfin was finished by the producer
+  } else {
+    hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
+                       ctx->p_stride, sw.U, a.slots, ctx->sc);
+    a.rsrc = ctx->sc.Rpart; a.rstride = a.slots;
+    a.rcount = sw.Gx <= 64 ? sw.Gx : 0;
+    if (a.rcount == 0)
+      hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
+                         ctx->sc.Rpart, a.slots, sw.Gx, ctx->sc.Rfin);
+  }
 #define LAQ_CALL(BB) launch_codes<BB>(grid, ctx->stream, a)
   LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
 #undef LAQ_CALL
@@ -787,6 +804,7 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
   if (((uintptr_t)codes_dev | (uintptr_t)theta_dev) & 15)
     return set_error(ctx, LAQ_EINVAL, "laq_server_step: codes_dev and theta_dev must be 16-byte aligned");
   ServerArgs a{};
+  ctx->radius_for = nullptr;   // the stored quantized gradients change below
   a.codes = codes_dev; a.R_in = R_dev; a.upload = upload_dev;
   a.H = ctx->H; a.nabla = ctx->nabla; a.theta = theta_dev; a.sc = ctx->sc;
   a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
@@ -803,6 +821,7 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
 
 int laq_get_state(laq_ctx* ctx, laq_state_view* v) {
   if (!ctx || !v) return LAQ_EINVAL;
+  ctx->radius_for = nullptr;   // the caller may overwrite the state through these pointers
   v->H_dev = ctx->H;
   v->nabla_dev = ctx->nabla;
   v->Ehat2_dev = ctx->sc.Ehat2;
@@ -867,6 +886,7 @@ int laq_set_model(laq_ctx* ctx, int32_t kind, const int32_t* dims, int32_t n_dim
   if (pp != ctx->p) return set_error(ctx, LAQ_EINVAL, "model has %lld parameters, context has p = %lld", (long long)pp, (long long)ctx->p);
   ctx->kind = kind;
   ctx->lambda = lambda;
+  ctx->radius_for = nullptr;
   ctx->X = nullptr; ctx->y = nullptr; ctx->model_ws = nullptr;
   return LAQ_OK;
 }
@@ -896,7 +916,17 @@ int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev) {
     return set_error(ctx, LAQ_ESTATE, "laq_worker_grads needs laq_set_model and laq_set_data");
   if (!theta_dev || !G_dev || (((uintptr_t)theta_dev | (uintptr_t)G_dev) & 15))
     return set_error(ctx, LAQ_EINVAL, "laq_worker_grads: null or misaligned pointer");
-  return worker_grads(ctx, theta_dev, G_dev);
+  ctx->radius_for = nullptr;
+  const int st = worker_grads(ctx, theta_dev, G_dev);
+  if (st == LAQ_OK && ctx->rprod_count > 0) {
+    if (ctx->rprod_count > 64) {
+      hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
+                         ctx->rprod, ctx->rprod_stride, ctx->rprod_count, ctx->sc.Rfin);
+      LAQ_HIP(ctx, hipGetLastError());
+    }
+    ctx->radius_for = G_dev;
+  }
+  return st;
 }
 
 }  // extern "C"

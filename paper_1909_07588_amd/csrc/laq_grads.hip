@@ -352,19 +352,37 @@ __global__ __launch_bounds__(kThreads) void binlog_grad_kernel(
   }
 }
 
-// G[m][i] = (sum over blocks, ascending) part[m][blk][i] / N + (N_m/N) lambda theta[i]
+// G[m][i] = (sum over blocks, ascending) part[m][blk][i] / N + (N_m/N) lambda theta[i].
+// Also leaves max_i |G[m][i] - H[m][i]| over this block's coordinates (raw bits)
+// in rprod[m][blockIdx.x]: the quantizer's radius without another pass over G.
 __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __restrict__ part,
                                                                const float* __restrict__ theta,
                                                                int64_t p, int64_t p_stride, int32_t n_blk,
                                                                float inv_N, float reg,
-                                                               float* __restrict__ G) {
+                                                               float* __restrict__ G,
+                                                               const float* __restrict__ H,
+                                                               uint32_t* __restrict__ rprod) {
   const int m = blockIdx.y;
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= p) return;
-  const float* pm = part + (int64_t)m * n_blk * p;
-  float s = 0.0f;
-  for (int k = 0; k < n_blk; ++k) s += pm[(int64_t)k * p + i];
-  G[(int64_t)m * p_stride + i] = fmaf(s, inv_N, reg * theta[i]);
+  uint32_t mx = 0;
+  if (i < p) {
+    const float* pm = part + (int64_t)m * n_blk * p;
+    float s = 0.0f;
+    for (int k = 0; k < n_blk; ++k) s += pm[(int64_t)k * p + i];
+    const float g = fmaf(s, inv_N, reg * theta[i]);
+    G[(int64_t)m * p_stride + i] = g;
+    mx = __float_as_uint(g - H[(int64_t)m * p_stride + i]) & 0x7fffffffu;
+  }
+  __shared__ uint32_t sm[kWaves];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)mx, off);
+    mx = mx > o ? mx : o;
+  }
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    rprod[(int64_t)m * gridDim.x + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
 // ------------------------------------------------------------------ host side
@@ -418,7 +436,9 @@ size_t model_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
   if (ctx->kind == LAQ_MODEL_BINLOG || ctx->kind == LAQ_MODEL_SOFTMAX) {
     int rpb;
     const int nb = logistic_blocks(ctx, N_m, &rpb);
-    return (size_t)ctx->M * nb * ctx->p * sizeof(float);
+    const size_t part = ((size_t)ctx->M * nb * ctx->p * sizeof(float) + 255) & ~(size_t)255;
+    const size_t fblocks = (size_t)((ctx->p + kThreads - 1) / kThreads);
+    return part + (size_t)ctx->M * fblocks * sizeof(uint32_t);
   }
   if (ctx->kind == LAQ_MODEL_MLP) return mlp_workspace_bytes(ctx, N_m);
   return 0;
@@ -482,8 +502,11 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   const float inv_N = (float)(1.0 / (double)N);
   const float reg = (float)(((double)ctx->N_m / (double)N) * (double)ctx->lambda);
   const dim3 fgrid((unsigned)((ctx->p + kThreads - 1) / kThreads), (unsigned)ctx->M);
+  const size_t part_bytes = ((size_t)ctx->M * nb * ctx->p * sizeof(float) + 255) & ~(size_t)255;
+  ctx->rprod = reinterpret_cast<uint32_t*>(ctx->model_ws + part_bytes);
+  ctx->rprod_stride = ctx->rprod_count = (int32_t)fgrid.x;
   hipLaunchKernelGGL(finish_grad_kernel, fgrid, dim3(kThreads), 0, ctx->stream, part, theta, ctx->p,
-                     ctx->p_stride, nb, inv_N, reg, G);
+                     ctx->p_stride, nb, inv_N, reg, G, ctx->H, ctx->rprod);
   LAQ_HIP(ctx, hipGetLastError());
   return LAQ_OK;
 }

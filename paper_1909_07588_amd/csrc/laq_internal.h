@@ -59,6 +59,13 @@ struct laq_ctx {
   laq::DeviceScalars sc{};
   size_t scalars_offset = 0, scalars_bytes = 0;
 
+  // Radius hand-over from laq_worker_grads to laq_quantize_skip: the gradient
+  // kernels' epilogues leave block maxima of |g - h| in rprod[m][0..rprod_count);
+  // valid only for the G pointer in radius_for and until the state changes.
+  const float* radius_for = nullptr;
+  uint32_t* rprod = nullptr;
+  int32_t rprod_stride = 0, rprod_count = 0;
+
   // model
   int32_t kind = LAQ_MODEL_NONE;
   float lambda = 0.f;

@@ -35,6 +35,11 @@ struct GemmArgs {
   const float* aux;    // bias[N] | mask[M][ldaux] | W[M][ldaux]
   int64_t ldaux;
   float scale, reg;
+  // EPI_GRAD only: stored quantized gradients laid out like C, and where to
+  // leave this block's max |C - H| (raw bits): rprod[z * rstride + rbase + block]
+  const float* Hq;
+  uint32_t* rprod;
+  int32_t rstride, rbase;
 };
 
 // K-major source S[k][x] -> LDS tile[kk][xx]
@@ -161,6 +166,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
   }
 
   // epilogue: lane holds C[i][j], j = lane%32, i = 8*(r/4) + 4*(lane/32) + r%4
+  uint32_t dmax = 0;
+  const float* Hq = (EPI == EPI_GRAD) ? g.Hq + (int64_t)blockIdx.z * g.sC : nullptr;
 #pragma unroll
   for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
@@ -180,10 +187,26 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
           v = g.aux[(int64_t)row * g.ldaux + col] > 0.0f ? v : 0.0f;
         } else {
           v = fmaf(v, g.scale, g.reg * g.aux[(int64_t)row * g.ldaux + col]);
+          const uint32_t db = __float_as_uint(v - Hq[(int64_t)row * g.ldc + col]) & 0x7fffffffu;
+          dmax = dmax > db ? dmax : db;
         }
         C[(int64_t)row * g.ldc + col] = v;
       }
     }
+  if (EPI == EPI_GRAD) {
+    // block maximum of |g - h| for the quantizer's radius (reuses the A tile's LDS)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const uint32_t o = (uint32_t)__shfl_xor((int)dmax, off);
+      dmax = dmax > o ? dmax : o;
+    }
+    uint32_t* red = reinterpret_cast<uint32_t*>(&As[0][0]);
+    if (lane == 0) red[wave] = dmax;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      g.rprod[(int64_t)blockIdx.z * g.rstride + g.rbase + blockIdx.y * gridDim.x + blockIdx.x] =
+          max(max(red[0], red[1]), max(red[2], red[3]));
+  }
 }
 
 // ------------------------------------------------------------------ class layer (C <= 16)
@@ -293,17 +316,34 @@ __global__ __launch_bounds__(kThreads) void class_wgrad_kernel(const float* __re
 }
 
 // G[m][off + j] = (sum over slabs, ascending) part[m][slab][j] * scale + reg * theta[off + j]
+// Also leaves the block maximum of |G - H| (raw bits) in rprod[m * rstride + rbase + blockIdx.x].
 __global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __restrict__ part, int32_t n_slab,
                                                                int64_t len, const float* __restrict__ theta_seg,
                                                                float scale, float reg, float* __restrict__ G,
-                                                               int64_t p_stride) {
+                                                               const float* __restrict__ Hq, int64_t p_stride,
+                                                               uint32_t* __restrict__ rprod, int32_t rstride,
+                                                               int32_t rbase) {
   const int m = blockIdx.y;
   const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (j >= len) return;
-  const float* pm = part + (int64_t)m * n_slab * len;
-  float s = 0.0f;
-  for (int k = 0; k < n_slab; ++k) s += pm[(int64_t)k * len + j];
-  G[(int64_t)m * p_stride + j] = fmaf(s, scale, reg * theta_seg[j]);
+  uint32_t mx = 0;
+  if (j < len) {
+    const float* pm = part + (int64_t)m * n_slab * len;
+    float s = 0.0f;
+    for (int k = 0; k < n_slab; ++k) s += pm[(int64_t)k * len + j];
+    const float gv = fmaf(s, scale, reg * theta_seg[j]);
+    G[(int64_t)m * p_stride + j] = gv;
+    mx = __float_as_uint(gv - Hq[(int64_t)m * p_stride + j]) & 0x7fffffffu;
+  }
+  __shared__ uint32_t sm[kThreads / 64];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)mx, off);
+    mx = mx > o ? mx : o;
+  }
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    rprod[(int64_t)m * rstride + rbase + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
 // Bias gradient: column sums of dZ over a slab of rows of worker m.
@@ -333,6 +373,8 @@ struct MlpPlan {
   int64_t dzc_off;                   // [S][C]
   int64_t part_off;                  // slab partial sums
   int32_t n_slab, rows_per_slab;
+  int64_t rprod_off;                 // [M][rprod_count] block maxima of |g - h|
+  int32_t rprod_count;
   int64_t total_floats;
 };
 
@@ -359,6 +401,16 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   const int64_t last_w = (int64_t)n.dims[n.n_layers - 1] * n.dims[n.n_layers];
   const int64_t part_len = last_w > widest ? last_w : widest;
   pl.part_off = off; off += align_up((int64_t)ctx->M * pl.n_slab * part_len, 64);
+  // one radius slot per block of every kernel that writes a segment of G
+  int64_t cnt = 0;
+  for (int l = 1; l <= n.n_layers; ++l) {
+    const int64_t in = n.dims[l - 1], out = n.dims[l];
+    if (l < n.n_layers) cnt += ((out + kBN - 1) / kBN) * ((in + kBM - 1) / kBM);   // weight-gradient GEMM
+    else cnt += (in * out + kThreads - 1) / kThreads;                              // class layer
+    cnt += (out + kThreads - 1) / kThreads;                                         // bias
+  }
+  pl.rprod_count = (int32_t)cnt;
+  pl.rprod_off = off; off += align_up((int64_t)ctx->M * cnt, 64);
   pl.total_floats = off;
   return pl;
 }
@@ -419,6 +471,11 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
                        Ain, ld_in, theta + n.offW[L - 1], theta + n.offB[L - 1], ctx->y, S, n.dims[L - 1], C, dZc);
   }
   float* part = ws + pl.part_off;
+  // radius slots: every kernel that writes a segment of G gets its own range
+  uint32_t* rprod = reinterpret_cast<uint32_t*>(ws + pl.rprod_off);
+  const int32_t rstride = pl.rprod_count;
+  int32_t rbase = 0;
+  ctx->rprod = rprod; ctx->rprod_stride = rstride; ctx->rprod_count = pl.rprod_count;
   // ---- class layer gradients
   {
     const int K = n.dims[L - 1];
@@ -426,15 +483,19 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     hipLaunchKernelGGL(class_wgrad_kernel, wg, dim3(kThreads), 0, ctx->stream, Ain, ld_in, dZc, N_m, K, C,
                        pl.rows_per_slab, part);
     const int64_t len = (int64_t)K * C;
-    hipLaunchKernelGGL(slab_finish_kernel, dim3((unsigned)((len + kThreads - 1) / kThreads), (unsigned)ctx->M),
-                       dim3(kThreads), 0, ctx->stream, part, pl.n_slab, len, theta + n.offW[L - 1], inv_N, reg,
-                       G + n.offW[L - 1], ctx->p_stride);
+    const unsigned wblocks = (unsigned)((len + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(slab_finish_kernel, dim3(wblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, part,
+                       pl.n_slab, len, theta + n.offW[L - 1], inv_N, reg, G + n.offW[L - 1],
+                       ctx->H + n.offW[L - 1], ctx->p_stride, rprod, rstride, rbase);
+    rbase += (int32_t)wblocks;
     const dim3 cg((unsigned)((C + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
     hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZc, (int64_t)C, N_m, C,
                        pl.rows_per_slab, part);
-    hipLaunchKernelGGL(slab_finish_kernel, dim3((unsigned)((C + kThreads - 1) / kThreads), (unsigned)ctx->M),
-                       dim3(kThreads), 0, ctx->stream, part, pl.n_slab, (int64_t)C, theta + n.offB[L - 1], inv_N,
-                       reg, G + n.offB[L - 1], ctx->p_stride);
+    const unsigned bblocks = (unsigned)((C + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(slab_finish_kernel, dim3(bblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, part,
+                       pl.n_slab, (int64_t)C, theta + n.offB[L - 1], inv_N, reg, G + n.offB[L - 1],
+                       ctx->H + n.offB[L - 1], ctx->p_stride, rprod, rstride, rbase);
+    rbase += (int32_t)bblocks;
   }
   // ---- backward through the hidden layers
   const float* dZnext = dZc;     // gradient w.r.t. pre-activations of layer l+1
@@ -471,20 +532,25 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
       g.vecB = vec_ok(g.B, g.ldb) && ((g.sB & 3) == 0);
       g.aux = theta + n.offW[l - 1]; g.ldaux = width;
       g.scale = inv_N; g.reg = reg;
+      g.Hq = ctx->H + n.offW[l - 1]; g.rprod = rprod; g.rstride = rstride; g.rbase = rbase;
       launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
+      rbase += ((g.N + kBN - 1) / kBN) * ((g.M + kBM - 1) / kBM);
     }
     // db_l(m) = column sums of dZ_l(m)
     {
       const dim3 cg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
       hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZl, (int64_t)width, N_m, width,
                          pl.rows_per_slab, part);
-      hipLaunchKernelGGL(slab_finish_kernel,
-                         dim3((unsigned)((width + kThreads - 1) / kThreads), (unsigned)ctx->M), dim3(kThreads), 0,
-                         ctx->stream, part, pl.n_slab, (int64_t)width, theta + n.offB[l - 1], inv_N, reg,
-                         G + n.offB[l - 1], ctx->p_stride);
+      const unsigned bblocks = (unsigned)((width + kThreads - 1) / kThreads);
+      hipLaunchKernelGGL(slab_finish_kernel, dim3(bblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
+                         part, pl.n_slab, (int64_t)width, theta + n.offB[l - 1], inv_N, reg, G + n.offB[l - 1],
+                         ctx->H + n.offB[l - 1], ctx->p_stride, rprod, rstride, rbase);
+      rbase += (int32_t)bblocks;
     }
     dZnext = dZl;
   }
+  if (rbase != pl.rprod_count)
+    return set_error(ctx, LAQ_EDEVICE, "internal: radius slot count mismatch (%d vs %d)", rbase, pl.rprod_count);
   LAQ_HIP(ctx, hipGetLastError());
   return LAQ_OK;
 }

@@ -342,3 +342,32 @@ def test_largest_network_widths_at_reduced_batch():
     G, G_ref = _grad_case(w)
     err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
     assert err.max() <= 1e-5, err
+
+
+def test_radius_handed_over_by_the_gradient_kernels_is_dropped_when_the_state_changes():
+    """laq_worker_grads leaves the radius for laq_quantize_skip; overwriting the stored
+    gradients through the state view in between must fall back to the radius pass."""
+    w = laq_synth.workload(2, scale=0.02)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    ctx, st, theta = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta0)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    Gd = ctx.alloc_G()
+    rng = np.random.default_rng(12)
+    ctx.laq_worker_grads(theta, Gd)
+    torch.cuda.synchronize()
+    G = Gd[:, :w.p].cpu().numpy()
+    msgs, _ = check_quantize(ctx, st, Gd, G)               # radius from the producer
+    st.H[:] = (G + 1e-3 * rng.standard_normal(G.shape)).astype(np.float32)
+    st.nabla[:] = st.H.sum(0)
+    push_state(ctx, st)                                    # state overwritten behind the library
+    msgs, _ = check_quantize(ctx, st, Gd, G)               # must see the new stored gradients
+    check_server(ctx, st, theta, msgs, G)
+    push_state(ctx, st)                                    # order-free part of the history entry
+    # a copy of G at another address: no hand-over either
+    G2 = Gd.clone()
+    ctx.laq_worker_grads(theta, Gd)
+    torch.cuda.synchronize()
+    Gn = Gd[:, :w.p].cpu().numpy()
+    G2.copy_(Gd)
+    check_quantize(ctx, st, G2, Gn)

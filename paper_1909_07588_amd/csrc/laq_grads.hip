@@ -131,28 +131,33 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
 // Both products of the softmax-regression gradient are skinny GEMMs:
 //   Z[16 rows][C] = X[16][F] Theta^T        and        Gacc[C][F] += R^T[C][16] X[16][F].
 // They map onto v_mfma_f32_16x16x4_f32 with the class dimension padded to 16.
-// One block (4 wavefronts) owns a range of rows and walks it in tiles of 16
-// rows: the tile is copied once from HBM to LDS (contiguous, coalesced,
-// prefetched into registers one tile ahead); for the logits the NW waves split
-// the feature dimension and their partial products are summed through LDS;
-// after the softmax the waves split the feature tiles of the rank-16 update
-// and keep their part of Gacc in registers for the whole row range.  LDS holds
-// one block per CU, so the block is wide (16 waves) to keep 4 waves per SIMD.
+// One block of 16 wavefronts owns a range of rows and walks it in tiles of 16
+// rows.  Tiles are copied once from HBM to LDS (coalesced, prefetched into
+// registers two tiles ahead, double-buffered in LDS).  For the logits the
+// waves split the feature dimension -- wave w always multiplies chunks
+// w, w+16, ..., so its fragments of Theta stay in registers for the whole
+// kernel -- and their partial products are summed through LDS.  The softmax
+// of tile n runs on 4 waves while the other 12 already form the logits of
+// tile n+1.  For the rank-16 update the waves split the feature tiles and keep
+// their part of Gacc in registers for the whole row range.  LDS allows one
+// block per CU, hence the wide block (4 waves per SIMD).
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-constexpr int kRT = 16;   // rows per tile
+constexpr int kRT = 16;          // rows per tile
+constexpr int kSmxWaves = 16;
 
-template <int NW, int TMAX>
-__global__ __launch_bounds__(64 * NW) void softmax_grad_mfma_kernel(
+template <int TMAX>
+__global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
     int64_t N_m, int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, int32_t ldsF,
     float* __restrict__ part) {
+  constexpr int NW = kSmxWaves, NT = 64 * NW;
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  float* Th = smem;                          // [C][ldsF], columns >= F are zero
-  float* Xs0 = Th + (int64_t)C * ldsF;       // [16][ldsF]
+  float* Xs0 = smem;                         // [16][ldsF]
   float* Xs1 = Xs0 + kRT * ldsF;
-  float* Zp = Xs1 + kRT * ldsF;              // [NW][16][16] partial logits
-  float* Rs = Zp + NW * 256;                 // [16][16] residuals P - Y
-  int* Ys = reinterpret_cast<int*>(Rs + 256);  // [2][16] labels of the current / next tile
+  float* Zp0 = Xs1 + kRT * ldsF;             // [NW][16][16] partial logits, two buffers
+  float* Zp1 = Zp0 + NW * 256;
+  float* Rs = Zp1 + NW * 256;                // [16][16] residuals P - Y
+  int* Ys = reinterpret_cast<int*>(Rs + 256);  // [2][16] labels, indexed like the X buffers
 
   const int m = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -161,26 +166,37 @@ __global__ __launch_bounds__(64 * NW) void softmax_grad_mfma_kernel(
   const int32_t* ym = y + (int64_t)m * N_m;
   const int nchunk = (F + 15) / 16, FP = nchunk * 16, nf4 = FP / 4;
 
-  constexpr int NT = 64 * NW;
-  for (int idx = tid; idx < C * FP; idx += NT) {
+  // Theta fragments of this wave's feature chunks (B operand of the logits): lane
+  // (class j = l16, quarter lq) holds Theta[j][16 t + 4 lq .. +3], zero past C or F.
+  // They go through LDS (staged in the first tile buffer) rather than straight
+  // from global memory into registers: the matrix instructions of the main loop
+  // then depend on LDS counters only and never wait behind the tile prefetch.
+  for (int idx = tid; idx < kRT * FP; idx += NT) {
     const int c = idx / FP, f = idx - c * FP;
-    Th[c * ldsF + f] = f < F ? theta[(int64_t)c * F + f] : 0.0f;
+    Xs0[c * ldsF + f] = (c < C && f < F) ? theta[(int64_t)c * F + f] : 0.0f;
   }
+  __syncthreads();
+  float4 thf[TMAX];
+#pragma unroll
+  for (int n = 0; n < TMAX; ++n) {
+    const int t = wave + NW * n;
+    thf[n] = t < nchunk ? *reinterpret_cast<const float4*>(&Xs0[l16 * ldsF + 16 * t + 4 * lq])
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __syncthreads();
 
   const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
   int64_t r_end = r_begin + rows_per_block;
   if (r_end > N_m) r_end = N_m;
+  const int64_t last_row = r_end - 1;
 
-  constexpr int PF = (kRT * NW * TMAX * 16 / 4 + NT - 1) / NT;   // float4 per lane per tile
-  // Tile prefetch: every lane issues PF unconditional 16-byte loads (row and
-  // column indices clamped into the matrix; rows are padded to ldx, a multiple
-  // of 4, so a float4 that starts below F stays inside its row) and the
-  // masking of rows >= r_end and columns >= F happens when the registers are
-  // written to LDS.  No branch and no wait sits between the loads and the
-  // matrix work they overlap with.
+  // Tile prefetch: PF unconditional 16-byte loads per lane (row and column
+  // clamped into the matrix; rows are padded to ldx, a multiple of 4, so a
+  // float4 that starts below F stays inside its row); rows >= r_end and columns
+  // >= F are zeroed when the registers are written to LDS.
+  constexpr int PF = (kRT * NW * TMAX * 16 / 4 + NT - 1) / NT;
   float4 pre[PF];
   int ypre = 0;
-  const int64_t last_row = r_end - 1;
   auto gload = [&](int64_t r0) {
     if (tid < kRT) ypre = ym[(r0 + tid < r_end) ? r0 + tid : last_row];
 #pragma unroll
@@ -212,41 +228,54 @@ __global__ __launch_bounds__(64 * NW) void softmax_grad_mfma_kernel(
       }
     }
   };
+  // logits of the tile in Xs: partial products of this wave's chunks -> Zp[wave]
+  auto logits = [&](const float* Xs, float* Zp) {
+    floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int n = 0; n < TMAX; ++n) {
+      const int t = wave + NW * n;
+      if (t < nchunk) {
+        const float4 a = *reinterpret_cast<const float4*>(&Xs[l16 * ldsF + 16 * t + 4 * lq]);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, thf[n].x, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, thf[n].z, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, acc1, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) Zp[wave * 256 + (4 * lq + r) * 16 + l16] = acc1[r];
+  };
 
   floatx4 acc2[TMAX];
 #pragma unroll
   for (int n = 0; n < TMAX; ++n) acc2[n] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+  // prologue: tile 0 in Xs0 with its logits in Zp0, tile 1 in Xs1
   gload(r_begin);
   lstore(Xs0, 0, r_begin);
+  const bool have1 = r_begin + kRT < r_end;
+  if (have1) gload(r_begin + kRT);
   __syncthreads();
+  logits(Xs0, Zp0);
+  if (have1) lstore(Xs1, 1, r_begin + kRT);
+  __syncthreads();
+
   int cur = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
-    float* Xs = cur ? Xs1 : Xs0;
-    const bool more = r0 + kRT < r_end;
-    if (more) gload(r0 + kRT);
+    float* Xc = cur ? Xs1 : Xs0;
+    float* Xn = cur ? Xs0 : Xs1;
+    float* Zc = cur ? Zp1 : Zp0;
+    float* Zn = cur ? Zp0 : Zp1;
+    const bool more1 = r0 + kRT < r_end;          // tile n+1 exists (already in Xn)
+    const bool more2 = r0 + 2 * kRT < r_end;      // tile n+2 exists
+    if (more2) gload(r0 + 2 * kRT);
 
-    // logits: wave w multiplies feature chunks t = w, w+NW, ...
-    floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-    for (int t = wave; t < nchunk; t += NW) {
-      const float4 a = *reinterpret_cast<const float4*>(&Xs[l16 * ldsF + 16 * t + 4 * lq]);
-      float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (l16 < C) b = *reinterpret_cast<const float4*>(&Th[l16 * ldsF + 16 * t + 4 * lq]);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc1, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc1, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc1, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc1, 0, 0, 0);
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) Zp[wave * 256 + (4 * lq + r) * 16 + l16] = acc1[r];
-    __syncthreads();
-
-    // softmax and residual: thread (i = tid/16, j = tid%16)
+    // softmax of tile n on waves 0..3 (lane = row i, class j), logits of tile n+1 on all
     if (tid < 256) {
       const int i = tid >> 4, j = tid & 15;
-      float z = Zp[tid];
+      float z = Zc[tid];
 #pragma unroll
-      for (int wv = 1; wv < NW; ++wv) z += Zp[wv * 256 + tid];
+      for (int wv = 1; wv < NW; ++wv) z += Zc[wv * 256 + tid];
       const bool valid = j < C;
       float zm = valid ? z : -INFINITY;
 #pragma unroll
@@ -255,14 +284,14 @@ __global__ __launch_bounds__(64 * NW) void softmax_grad_mfma_kernel(
       float den = e;
 #pragma unroll
       for (int off = 8; off > 0; off >>= 1) den += __shfl_xor(den, off);
-      const int64_t gr = r0 + i;
       float rv = 0.0f;
-      if (valid && gr < r_end) rv = e / den - (j == Ys[cur * kRT + i] ? 1.0f : 0.0f);
+      if (valid && r0 + i < r_end) rv = e / den - (j == Ys[cur * kRT + i] ? 1.0f : 0.0f);
       Rs[tid] = rv;
     }
+    if (more1) logits(Xn, Zn);
     __syncthreads();
 
-    // rank-16 update: wave w owns feature tiles ft = w, w+NW, ...
+    // rank-16 update with tile n: wave w owns feature tiles ft = w, w+NW, ...
     float ar[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) ar[u] = Rs[(4 * u + lq) * 16 + l16];
@@ -272,12 +301,13 @@ __global__ __launch_bounds__(64 * NW) void softmax_grad_mfma_kernel(
       if (ft < nchunk) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float b = Xs[(4 * u + lq) * ldsF + 16 * ft + l16];
+          const float b = Xc[(4 * u + lq) * ldsF + 16 * ft + l16];
           acc2[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[u], b, acc2[n], 0, 0, 0);
         }
       }
     }
-    if (more) lstore(cur ? Xs0 : Xs1, cur ^ 1, r0 + kRT);
+    __syncthreads();                               // tile n fully consumed: its buffer is free
+    if (more2) lstore(Xc, cur, r0 + 2 * kRT);
     __syncthreads();
     cur ^= 1;
   }
@@ -387,8 +417,6 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
 
 // ------------------------------------------------------------------ host side
 
-constexpr int kSmxWaves = 16;
-
 // LDS layout of the matrix-core softmax kernel: row stride (floats) and bytes; 0 if it does not fit.
 static size_t softmax_mfma_lds(const laq_ctx* ctx, int* ldsF_out) {
   if (ctx->kind != LAQ_MODEL_SOFTMAX || ctx->C > 16) return 0;
@@ -396,21 +424,21 @@ static size_t softmax_mfma_lds(const laq_ctx* ctx, int* ldsF_out) {
   if (FP > 16 * kSmxWaves * 4) return 0;
   const int pad = (20 - FP % 32 + 32) % 32;       // row stride = 20 (mod 32) banks: conflict-free b128 reads
   const int ldsF = FP + pad;
-  const size_t bytes = ((size_t)(ctx->C + 2 * kRT) * ldsF + (kSmxWaves + 1) * 256 + 2 * kRT) * sizeof(float);
-  if (bytes > 160 * 1024) return 0;
   if (ldsF_out) *ldsF_out = ldsF;
-  return bytes;
+  const size_t bytes = ((size_t)2 * kRT * ldsF + (2 * kSmxWaves + 1) * 256 + 2 * kRT) * sizeof(float);
+  return bytes <= 160 * 1024 ? bytes : 0;
 }
 
 static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block) {
   if (softmax_mfma_lds(ctx, nullptr)) {
-    // one block per CU at most (LDS-bound occupancy), whole tiles of 16 rows per block
+    // one block per CU at most (LDS-bound occupancy), whole row tiles per block
+    const int RT = kRT;
     int64_t want = ctx->n_cu / ctx->M;
     if (want < 1) want = 1;
-    const int64_t tiles = (N_m + kRT - 1) / kRT;
+    const int64_t tiles = (N_m + RT - 1) / RT;
     if (want > tiles) want = tiles;
     const int64_t tpb = (tiles + want - 1) / want;
-    *rows_per_block = (int)(tpb * kRT);
+    *rows_per_block = (int)(tpb * RT);
     return (int)((tiles + tpb - 1) / tpb);
   }
   // about two blocks per CU over all workers, at least 4 rows per wave
@@ -470,7 +498,7 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     const int nchunk = (ctx->F + 15) / 16;
 #define LAQ_SMM(T)                                                                                     \
   do {                                                                                                 \
-    auto kfn = softmax_grad_mfma_kernel<kSmxWaves, T>;                                                 \
+    auto kfn = softmax_grad_mfma_kernel<T>;                                                            \
     LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                               \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
     hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta, ctx->X, ctx->y,   \

@@ -20,7 +20,7 @@ namespace laq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128, kBN = 128, kBK = 16, kLd = kBM + 4;
+constexpr int kBK = 16;   // K tile; block tile is BT x BT with BT = 128 or 64
 
 enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2 };
 
@@ -42,13 +42,15 @@ struct GemmArgs {
   int32_t rstride, rbase;
 };
 
-// K-major source S[k][x] -> LDS tile[kk][xx]
+// K-major source S[k][x] -> LDS tile[kk][xx]; NL = BT/64 float4 per lane
+template <int NL>
 __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, int X, int k0, int x0,
-                                            int vec, float4 (&r)[2]) {
+                                            int vec, float4 (&r)[NL]) {
   const int t = threadIdx.x;
+  constexpr int TPR = 16 * NL;          // lanes per tile row
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int kk = t / 32 + 8 * i, xx = (t % 32) * 4;
+  for (int i = 0; i < NL; ++i) {
+    const int kk = t / TPR + (kThreads / TPR) * i, xx = (t % TPR) * 4;
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (k < K) {
@@ -65,21 +67,24 @@ __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, i
     r[i] = v;
   }
 }
-__device__ __forceinline__ void store_direct(float (*tile)[kLd], const float4 (&r)[2]) {
+template <int NL>
+__device__ __forceinline__ void store_direct(float (*tile)[64 * NL + 4], const float4 (&r)[NL]) {
   const int t = threadIdx.x;
+  constexpr int TPR = 16 * NL;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int kk = t / 32 + 8 * i, xx = (t % 32) * 4;
+  for (int i = 0; i < NL; ++i) {
+    const int kk = t / TPR + (kThreads / TPR) * i, xx = (t % TPR) * 4;
     *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
   }
 }
 
 // X-major source S[x][k] -> LDS tile[kk][xx] (transposed on the way in)
+template <int NL>
 __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int K, int X, int k0, int x0,
-                                                int vec, float4 (&r)[2]) {
+                                                int vec, float4 (&r)[NL]) {
   const int t = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < NL; ++i) {
     const int xx = t / 4 + 64 * i, kk = (t % 4) * 4;
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -97,10 +102,11 @@ __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int 
     r[i] = v;
   }
 }
-__device__ __forceinline__ void store_transposed(float (*tile)[kLd], const float4 (&r)[2]) {
+template <int NL>
+__device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], const float4 (&r)[NL]) {
   const int t = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < NL; ++i) {
     const int xx = t / 4 + 64 * i, kk = (t % 4) * 4;
     tile[kk + 0][xx] = r[i].x;
     tile[kk + 1][xx] = r[i].y;
@@ -109,8 +115,10 @@ __device__ __forceinline__ void store_transposed(float (*tile)[kLd], const float
   }
 }
 
-template <bool TA, bool TB, int EPI>
+template <bool TA, bool TB, int EPI, int NL>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
+  constexpr int BT = 64 * NL, kLd = BT + 4, WT = 32 * NL;   // block tile, LDS row stride, wave tile
+  constexpr int kBM = BT, kBN = BT;
   __shared__ __attribute__((aligned(16))) float As[kBK][kLd];
   __shared__ __attribute__((aligned(16))) float Bs[kBK][kLd];
   const float* A = g.A + (int64_t)blockIdx.z * g.sA;
@@ -120,24 +128,24 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wy = wave >> 1, wx = wave & 1;
 
-  floatx16 acc[2][2];
+  floatx16 acc[NL][NL];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NL; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NL; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  float4 ra[2], rb[2];
+  float4 ra[NL], rb[NL];
   auto fetch = [&](int k0) {
-    if (TA) load_direct(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    else load_transposed(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    if (TB) load_transposed(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
-    else load_direct(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    if (TA) load_direct<NL>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    else load_transposed<NL>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    if (TB) load_transposed<NL>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    else load_direct<NL>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
   };
   auto stage = [&]() {
-    if (TA) store_direct(As, ra); else store_transposed(As, ra);
-    if (TB) store_transposed(Bs, rb); else store_direct(Bs, rb);
+    if (TA) store_direct<NL>(As, ra); else store_transposed<NL>(As, ra);
+    if (TB) store_transposed<NL>(Bs, rb); else store_direct<NL>(Bs, rb);
   };
 
   fetch(0);
@@ -149,14 +157,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
     if (more) fetch(k0 + kBK);
 #pragma unroll
     for (int kk = 0; kk < kBK; kk += 2) {
-      const float a0 = As[kk + kh][wy * 64 + li];
-      const float a1 = As[kk + kh][wy * 64 + 32 + li];
-      const float b0 = Bs[kk + kh][wx * 64 + li];
-      const float b1 = Bs[kk + kh][wx * 64 + 32 + li];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      float av[NL], bv[NL];
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        av[i] = As[kk + kh][wy * WT + 32 * i + li];
+        bv[i] = Bs[kk + kh][wx * WT + 32 * i + li];
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i)
+#pragma unroll
+        for (int j = 0; j < NL; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
     if (more) {
@@ -169,16 +180,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
   uint32_t dmax = 0;
   const float* Hq = (EPI == EPI_GRAD) ? g.Hq + (int64_t)blockIdx.z * g.sC : nullptr;
 #pragma unroll
-  for (int ti = 0; ti < 2; ++ti)
+  for (int ti = 0; ti < NL; ++ti)
 #pragma unroll
-    for (int tj = 0; tj < 2; ++tj) {
-      const int col = n0 + wx * 64 + tj * 32 + li;
+    for (int tj = 0; tj < NL; ++tj) {
+      const int col = n0 + wx * WT + tj * 32 + li;
       if (col >= g.N) continue;
       float bias = 0.0f;
       if (EPI == EPI_BIAS_RELU) bias = g.aux[col];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wy * 64 + ti * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+        const int row = m0 + wy * WT + ti * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
         if (row >= g.M) continue;
         float v = acc[ti][tj][r];
         if (EPI == EPI_BIAS_RELU) {
@@ -366,6 +377,13 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float* __restric
 
 static inline int64_t align_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
+// Block tile: 128 x 128 when that still gives every CU a few blocks, else 64 x 64.
+static int gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch) {
+  const int64_t blocks128 = ((Mr + 127) / 128) * ((Nc + 127) / 128) * batch;
+  return blocks128 >= (int64_t)ctx->n_cu * 3 ? 128 : 64;
+}
+
+
 struct MlpPlan {
   int64_t S;
   int64_t act_off[LAQ_MAX_LAYERS];   // activations after hidden layer l (l = 1..L-1), floats
@@ -405,7 +423,10 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   int64_t cnt = 0;
   for (int l = 1; l <= n.n_layers; ++l) {
     const int64_t in = n.dims[l - 1], out = n.dims[l];
-    if (l < n.n_layers) cnt += ((out + kBN - 1) / kBN) * ((in + kBM - 1) / kBM);   // weight-gradient GEMM
+    if (l < n.n_layers) {                                                         // weight-gradient GEMM
+      const int bt = gemm_tile(ctx, in, out, ctx->M);
+      cnt += ((out + bt - 1) / bt) * ((in + bt - 1) / bt);
+    }
     else cnt += (in * out + kThreads - 1) / kThreads;                              // class layer
     cnt += (out + kThreads - 1) / kThreads;                                         // bias
   }
@@ -421,8 +442,10 @@ size_t mlp_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
 
 template <bool TA, bool TB, int EPI>
 static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch) {
-  const dim3 grid((unsigned)((g.N + kBN - 1) / kBN), (unsigned)((g.M + kBM - 1) / kBM), (unsigned)batch);
-  hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI>), grid, dim3(kThreads), 0, ctx->stream, g);
+  const int bt = gemm_tile(ctx, g.M, g.N, batch);
+  const dim3 grid((unsigned)((g.N + bt - 1) / bt), (unsigned)((g.M + bt - 1) / bt), (unsigned)batch);
+  if (bt == 128) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2>), grid, dim3(kThreads), 0, ctx->stream, g);
+  else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1>), grid, dim3(kThreads), 0, ctx->stream, g);
 }
 
 static inline int vec_ok(const void* p, int64_t ld) { return (((uintptr_t)p & 15) == 0 && (ld & 3) == 0) ? 1 : 0; }
@@ -534,7 +557,8 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
       g.scale = inv_N; g.reg = reg;
       g.Hq = ctx->H + n.offW[l - 1]; g.rprod = rprod; g.rstride = rstride; g.rbase = rbase;
       launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
-      rbase += ((g.N + kBN - 1) / kBN) * ((g.M + kBM - 1) / kBM);
+      const int bt = gemm_tile(ctx, g.M, g.N, ctx->M);
+      rbase += ((g.N + bt - 1) / bt) * ((g.M + bt - 1) / bt);
     }
     // db_l(m) = column sums of dZ_l(m)
     {

@@ -173,6 +173,7 @@ struct QuantArgs {
   DeviceScalars sc;
   int64_t p, p_stride, w_stride;
   int32_t M, D, t_bar, eps_K, slots, U;
+  int32_t fused_decide;   // 1: the code pass's last block per worker applies the skip rule
   // radius source: either the finished value Rfin[m] (rcount == 0) or at most 64
   // block maxima rsrc[m * rstride + i], i < rcount, combined on the fly
   const uint32_t* rsrc;
@@ -180,6 +181,9 @@ struct QuantArgs {
   float alpha;
   uint32_t mode;
 };
+
+template <int B>
+__device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t n_slots);
 
 // One coordinate of eqs. 5-6 plus its contributions to the two squared norms.
 template <int B>
@@ -305,27 +309,41 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     const unsigned long long n64 = wave_sum_u64((unsigned long long)accN);
     if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
     __syncthreads();
+    __shared__ bool last_s;
     if (threadIdx.x == 0) {
       const int64_t slot = (int64_t)m * a.slots + blockIdx.x;
       a.sc.Spart[slot] = (smS[0] + smS[1]) + (smS[2] + smS[3]);
       a.sc.Npart[slot] = (smN[0] + smN[1]) + (smN[2] + smN[3]);
+      if (a.fused_decide) {
+        // few blocks per worker: the last one to finish applies the skip rule
+        // (saves a launch; with thousands of blocks the counter would serialise)
+        __threadfence();
+        last_s = (atomicAdd(&a.sc.ticket[m], 1u) == gridDim.x - 1);
+      }
+    }
+    if (a.fused_decide) {
+      __syncthreads();
+      if (last_s) {
+        __threadfence();
+        if (threadIdx.x == 0) a.sc.ticket[m] = 0;
+        decide_worker<B>(a, m, (int32_t)gridDim.x);
+      }
     }
   }
 }
 
 // Totals of the block partials (integers: order-free) and the skip rule
-// (eqs. 7a-7b) in binary64 with a fixed operation order; one block per worker.
+// (eqs. 7a-7b) in binary64 with a fixed operation order; run by one block for worker m.
 template <int B>
-__global__ __launch_bounds__(kThreads) void decide_kernel(QuantArgs a, int32_t n_slots) {
+__device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t n_slots) {
   constexpr int L = (1 << B) - 1;
   __shared__ unsigned long long smS[kThreads / 64], smN[kThreads / 64];
   __shared__ uint32_t smR[kThreads / 64];
-  const int m = blockIdx.x;
   unsigned long long s64 = 0, n64 = 0;
   uint32_t rb = 0;
   for (int i = threadIdx.x; i < n_slots; i += kThreads) {
-    s64 += a.sc.Spart[(int64_t)m * a.slots + i];
-    n64 += a.sc.Npart[(int64_t)m * a.slots + i];
+    s64 += __hip_atomic_load(&a.sc.Spart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    n64 += __hip_atomic_load(&a.sc.Npart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   if (a.rcount > 0) {
     if ((int)threadIdx.x < a.rcount) rb = a.rsrc[(int64_t)m * a.rstride + threadIdx.x];
@@ -365,6 +383,11 @@ __global__ __launch_bounds__(kThreads) void decide_kernel(QuantArgs a, int32_t n
   a.sc.E2[m] = E2;
   a.sc.lhs[m] = lhs;
   a.sc.rhs[m] = rhs;
+}
+
+template <int B>
+__global__ __launch_bounds__(kThreads) void decide_kernel(QuantArgs a, int32_t n_slots) {
+  decide_worker<B>(a, blockIdx.x, n_slots);
 }
 
 // ------------------------------------------------------------------ server step
@@ -552,7 +575,7 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
 
 struct Layout {
   size_t H, nabla, scalars, total;
-  size_t Rpart, Spart, Npart, Rfin, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
+  size_t Rpart, Spart, Npart, Rfin, ticket, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
       dtheta2, xi, srv_part, scalars_end;
 };
 
@@ -603,6 +626,7 @@ static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   l.Spart = take((size_t)M * slots * 8);
   l.Npart = take((size_t)M * slots * 8);
   l.Rfin = take((size_t)M * 4);
+  l.ticket = take((size_t)M * 4);
   l.Sq = take((size_t)M * 8);
   l.E2 = take((size_t)M * 8);
   l.lhs = take((size_t)M * 8);
@@ -632,7 +656,8 @@ static bool valid_sizes(int32_t M, int64_t p, int32_t b, int32_t D) {
 template <int B>
 static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
   hipLaunchKernelGGL(codes_kernel<B>, grid, dim3(kThreads), 0, s, a);
-  hipLaunchKernelGGL(decide_kernel<B>, dim3((unsigned)a.M), dim3(kThreads), 0, s, a, (int32_t)grid.x);
+  if (!a.fused_decide)
+    hipLaunchKernelGGL(decide_kernel<B>, dim3((unsigned)a.M), dim3(kThreads), 0, s, a, (int32_t)grid.x);
 }
 template <int B>
 static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArgs& a) {
@@ -713,6 +738,7 @@ int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const 
   s.Spart = (unsigned long long*)(w + l.Spart);
   s.Npart = (unsigned long long*)(w + l.Npart);
   s.Rfin = (uint32_t*)(w + l.Rfin);
+  s.ticket = (uint32_t*)(w + l.ticket);
   s.Sq = (long long*)(w + l.Sq);
   s.E2 = (double*)(w + l.E2);
   s.lhs = (double*)(w + l.lhs);
@@ -775,6 +801,7 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   const Sweep sw = make_sweep(ctx->p, ctx->M);
   const dim3 grid((unsigned)sw.Gx, (unsigned)ctx->M);
   a.U = sw.U;
+  a.fused_decide = sw.Gx <= 64;
   if (ctx->radius_for == G_dev && G_dev != nullptr) {
     // laq_worker_grads produced these gradients and left the block maxima of
     // |g - h| behind: the radius pass (a full read of g and h) is not needed

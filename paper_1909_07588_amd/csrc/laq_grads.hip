@@ -398,6 +398,7 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
   if (i < p) {
     const float* pm = part + (int64_t)m * n_blk * p;
     float s = 0.0f;
+#pragma unroll 8
     for (int k = 0; k < n_blk; ++k) s += pm[(int64_t)k * p + i];
     const float g = fmaf(s, inv_N, reg * theta[i]);
     G[(int64_t)m * p_stride + i] = g;

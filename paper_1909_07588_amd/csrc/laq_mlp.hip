@@ -224,53 +224,78 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
 
 constexpr int kCMax = 16;
 
-// logits z = a W + b, P = softmax(z), dZ = P - onehot(y); one wavefront per row.
-// W[K][C] is staged in LDS; lanes split K.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Class layer forward + loss gradient: Z[16 rows][C] = A[16][K] W[K][C] + b on
+// v_mfma_f32_16x16x4_f32 (classes padded to 16), P = softmax(Z), dZ = P - onehot(y).
+// A wavefront owns tiles of 16 rows and works alone: lane (row i = lane%16,
+// quarter q = lane/16) streams A[i][16t + 4q .. +3] straight from HBM (each
+// activation is used once) while W^T sits in LDS as the B operand; the softmax
+// is a 16-lane butterfly on the accumulator layout.  No barrier in the loop.
 __global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __restrict__ Aact, int64_t lda,
                                                                  const float* __restrict__ W,
                                                                  const float* __restrict__ bias,
                                                                  const int32_t* __restrict__ y, int64_t S,
-                                                                 int32_t K, int32_t C,
+                                                                 int32_t K, int32_t C, int32_t ldsK, int32_t vec,
                                                                  float* __restrict__ dZ) {
-  extern __shared__ float Ws[];   // [K][C]
-  for (int i = threadIdx.x; i < K * C; i += kThreads) Ws[i] = W[i];
+  extern __shared__ __attribute__((aligned(16))) float Wt[];   // [C][ldsK], columns >= K zero
+  const int nchunk = (K + 15) / 16, KP = nchunk * 16;
+  for (int idx = threadIdx.x; idx < C * KP; idx += kThreads) {
+    const int c = idx / KP, k = idx - c * KP;
+    Wt[c * ldsK + k] = k < K ? W[(int64_t)k * C + c] : 0.0f;
+  }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int64_t n_tiles = (S + 15) / 16;
   const int64_t stride = (int64_t)gridDim.x * (kThreads / 64);
-  for (int64_t row = (int64_t)blockIdx.x * (kThreads / 64) + wave; row < S; row += stride) {
-    const float* a = Aact + row * lda;
-    float z[kCMax];
-#pragma unroll
-    for (int c = 0; c < kCMax; ++c) z[c] = 0.0f;
-    for (int k = lane; k < K; k += 64) {
-      const float av = a[k];
-      const float* w = Ws + k * C;
-#pragma unroll
-      for (int c = 0; c < kCMax; ++c)
-        if (c < C) z[c] = fmaf(av, w[c], z[c]);
-    }
-#pragma unroll
-    for (int c = 0; c < kCMax; ++c)
-      if (c < C) {
-        float v = z[c];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-        z[c] = v + bias[c];
+  const float bj = l16 < C ? bias[l16] : 0.0f;
+  for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < n_tiles; tile += stride) {
+    const int64_t row0 = tile * 16;
+    int64_t ra = row0 + l16;
+    ra = ra < S ? ra : S - 1;
+    const float* arow = Aact + ra * lda + 4 * lq;
+    const float* wrow = Wt + l16 * ldsK + 4 * lq;
+    floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+    auto chunk = [&](int t, floatx4& acc) {
+      const int k = 16 * t + 4 * lq;
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (vec && k + 3 < K) {
+        a = *reinterpret_cast<const float4*>(arow + 16 * t);
+      } else {
+        if (k < K) a.x = arow[16 * t];
+        if (k + 1 < K) a.y = arow[16 * t + 1];
+        if (k + 2 < K) a.z = arow[16 * t + 2];
+        if (k + 3 < K) a.w = arow[16 * t + 3];
       }
-    float zmax = z[0];
+      float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (l16 < C) b = *reinterpret_cast<const float4*>(wrow + 16 * t);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc, 0, 0, 0);
+    };
+    int t = 0;
+#pragma unroll 2
+    for (; t + 1 < nchunk; t += 2) {   // two independent accumulator chains
+      chunk(t, acc0);
+      chunk(t + 1, acc1);
+    }
+    if (t < nchunk) chunk(t, acc0);
+    // lane holds Z[4 lq + r][l16], r = 0..3
 #pragma unroll
-    for (int c = 1; c < kCMax; ++c)
-      if (c < C) zmax = fmaxf(zmax, z[c]);
-    float den = 0.0f;
+    for (int r = 0; r < 4; ++r) {
+      const int64_t row = row0 + 4 * lq + r;
+      const bool valid = l16 < C;
+      const float z = acc0[r] + acc1[r] + bj;
+      float zm = valid ? z : -INFINITY;
 #pragma unroll
-    for (int c = 0; c < kCMax; ++c)
-      if (c < C) { z[c] = expf(z[c] - zmax); den += z[c]; }
-    const float inv = 1.0f / den;
-    const int label = y[row];
-    if (lane == 0) {
+      for (int off = 8; off > 0; off >>= 1) zm = fmaxf(zm, __shfl_xor(zm, off));
+      const float e = valid ? expf(z - zm) : 0.0f;
+      float den = e;
 #pragma unroll
-      for (int c = 0; c < kCMax; ++c)
-        if (c < C) dZ[row * C + c] = z[c] * inv - (c == label ? 1.0f : 0.0f);
+      for (int off = 8; off > 0; off >>= 1) den += __shfl_xor(den, off);
+      if (valid && row < S) dZ[row * C + l16] = e / den - (l16 == y[row] ? 1.0f : 0.0f);
     }
   }
 }
@@ -462,9 +487,6 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   const int64_t N = S;
   const float inv_N = (float)(1.0 / (double)N);
   const float reg = (float)(((double)N_m / (double)N) * (double)ctx->lambda);
-  const size_t class_smem = (size_t)n.dims[L - 1] * C * sizeof(float);
-  if (class_smem > 150 * 1024)
-    return set_error(ctx, LAQ_EINVAL, "MLP: last hidden width * classes must fit 150 KB of LDS");
 
   // ---- forward through the hidden layers: A_l = relu(A_{l-1} W_l + b_l)
   const float* Ain = ctx->X;
@@ -484,14 +506,22 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   // ---- class layer forward + softmax cross-entropy: dZ_L = P - Y
   float* dZc = ws + pl.dzc_off;
   {
-    int64_t blocks = (S + 3) / 4;
+    const int K = n.dims[L - 1];
+    const int KP = (K + 15) / 16 * 16;
+    const int ldsK = KP + (20 - KP % 32 + 32) % 32;   // row stride = 20 (mod 32) banks
+    const size_t smem = (size_t)C * ldsK * sizeof(float);
+    if (smem > 160 * 1024)
+      return set_error(ctx, LAQ_EINVAL, "MLP: last hidden width * classes does not fit LDS");
+    const int64_t tiles = (S + 15) / 16;
+    int64_t blocks = (tiles + 3) / 4;
     const int64_t cap = (int64_t)ctx->n_cu * 8;
     if (blocks > cap) blocks = cap;
-    if (class_smem > 48 * 1024)
+    if (smem > 48 * 1024)
       LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(class_forward_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)class_smem));
-    hipLaunchKernelGGL(class_forward_kernel, dim3((unsigned)blocks), dim3(kThreads), class_smem, ctx->stream,
-                       Ain, ld_in, theta + n.offW[L - 1], theta + n.offB[L - 1], ctx->y, S, n.dims[L - 1], C, dZc);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL(class_forward_kernel, dim3((unsigned)blocks), dim3(kThreads), smem, ctx->stream, Ain,
+                       ld_in, theta + n.offW[L - 1], theta + n.offB[L - 1], ctx->y, S, K, C, ldsK,
+                       vec_ok(Ain, ld_in), dZc);
   }
   float* part = ws + pl.part_off;
   // radius slots: every kernel that writes a segment of G gets its own range

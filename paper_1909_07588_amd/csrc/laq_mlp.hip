@@ -20,7 +20,6 @@ namespace laq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBK = 16;   // K tile; block tile is BT x BT with BT = 128 or 64
 
 enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2 };
 
@@ -42,14 +41,17 @@ struct GemmArgs {
   int32_t rstride, rbase;
 };
 
-// K-major source S[k][x] -> LDS tile[kk][xx]; NL = BT/64 float4 per lane
-template <int NL>
+// Tile loaders.  A block tile is BT = 64 NL wide and BK deep; each lane moves
+// NV = NL BK / 16 float4 per operand.  LDS tiles are K-major: tile[kk][xx].
+
+// K-major source S[k][x]
+template <int NL, int BK>
 __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, int X, int k0, int x0,
-                                            int vec, float4 (&r)[NL]) {
+                                            int vec, float4 (&r)[NL * BK / 16]) {
   const int t = threadIdx.x;
   constexpr int TPR = 16 * NL;          // lanes per tile row
 #pragma unroll
-  for (int i = 0; i < NL; ++i) {
+  for (int i = 0; i < NL * BK / 16; ++i) {
     const int kk = t / TPR + (kThreads / TPR) * i, xx = (t % TPR) * 4;
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -67,25 +69,26 @@ __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, i
     r[i] = v;
   }
 }
-template <int NL>
-__device__ __forceinline__ void store_direct(float (*tile)[64 * NL + 4], const float4 (&r)[NL]) {
+template <int NL, int BK>
+__device__ __forceinline__ void store_direct(float (*tile)[64 * NL + 4], const float4 (&r)[NL * BK / 16]) {
   const int t = threadIdx.x;
   constexpr int TPR = 16 * NL;
 #pragma unroll
-  for (int i = 0; i < NL; ++i) {
+  for (int i = 0; i < NL * BK / 16; ++i) {
     const int kk = t / TPR + (kThreads / TPR) * i, xx = (t % TPR) * 4;
     *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
   }
 }
 
-// X-major source S[x][k] -> LDS tile[kk][xx] (transposed on the way in)
-template <int NL>
+// X-major source S[x][k] (transposed on the way into LDS)
+template <int NL, int BK>
 __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int K, int X, int k0, int x0,
-                                                int vec, float4 (&r)[NL]) {
+                                                int vec, float4 (&r)[NL * BK / 16]) {
   const int t = threadIdx.x;
+  constexpr int LPR = BK / 4;           // lanes per source row
 #pragma unroll
-  for (int i = 0; i < NL; ++i) {
-    const int xx = t / 4 + 64 * i, kk = (t % 4) * 4;
+  for (int i = 0; i < NL * BK / 16; ++i) {
+    const int xx = t / LPR + (kThreads / LPR) * i, kk = (t % LPR) * 4;
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (x < X) {
@@ -102,12 +105,13 @@ __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int 
     r[i] = v;
   }
 }
-template <int NL>
-__device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], const float4 (&r)[NL]) {
+template <int NL, int BK>
+__device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], const float4 (&r)[NL * BK / 16]) {
   const int t = threadIdx.x;
+  constexpr int LPR = BK / 4;
 #pragma unroll
-  for (int i = 0; i < NL; ++i) {
-    const int xx = t / 4 + 64 * i, kk = (t % 4) * 4;
+  for (int i = 0; i < NL * BK / 16; ++i) {
+    const int xx = t / LPR + (kThreads / LPR) * i, kk = (t % LPR) * 4;
     tile[kk + 0][xx] = r[i].x;
     tile[kk + 1][xx] = r[i].y;
     tile[kk + 2][xx] = r[i].z;
@@ -115,12 +119,71 @@ __device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], con
   }
 }
 
-template <bool TA, bool TB, int EPI, int NL>
+// Fast path (operand rows 16-byte aligned, X and K multiples of 4): every float4
+// is wholly inside or wholly outside the operand, so a lane keeps one clamped
+// source pointer per float4, loads unconditionally and zeroes what lies outside.
+// No branch sits between the loads and the matrix instructions they overlap.
+template <int NL, int BK, bool XMAJOR>
+struct FastLoader {
+  static constexpr int NV = NL * BK / 16;
+  const float* p[NV];   // source address of this lane's float4 in K tile 0 (clamped into the operand)
+  int kk[NV];           // its k offset inside the tile
+  bool xin[NV];         // its row/column lies inside the operand
+  int64_t kstep;        // address advance per K tile
+  int K;
+
+  __device__ __forceinline__ void init(const float* S, int64_t ld, int K_, int X, int x0) {
+    const int t = threadIdx.x;
+    K = K_;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int kq, xx;
+      if (XMAJOR) {
+        constexpr int LPR = BK / 4;
+        xx = t / LPR + (kThreads / LPR) * i; kq = (t % LPR) * 4;
+      } else {
+        constexpr int TPR = 16 * NL;
+        kq = t / TPR + (kThreads / TPR) * i; xx = (t % TPR) * 4;
+      }
+      kk[i] = kq;
+      const int x = x0 + xx;
+      xin[i] = x < X;
+      const int xc = xin[i] ? x : 0;
+      p[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
+    }
+    kstep = XMAJOR ? BK : (int64_t)BK * ld;
+  }
+  // loads K tile number `tile`; rows of k >= K are redirected to tile 0 (in bounds) and zeroed
+  __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) const {
+    const int k0 = tile * BK;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const bool kin = k0 + kk[i] < K;
+      const float* src = p[i] + (kin ? (int64_t)tile * kstep : 0);
+      float4 v = *reinterpret_cast<const float4*>(src);
+      const bool ok = kin && xin[i];
+      v.x = ok ? v.x : 0.0f; v.y = ok ? v.y : 0.0f; v.z = ok ? v.z : 0.0f; v.w = ok ? v.w : 0.0f;
+      r[i] = v;
+    }
+  }
+};
+
+#ifndef LAQ_GEMM_BK
+#define LAQ_GEMM_BK 16
+#endif
+#ifndef LAQ_GEMM_NBUF
+#define LAQ_GEMM_NBUF 2
+#endif
+
+// C = op(A) op(B) with a fused epilogue.  NBUF = 2: the next K tile is written to
+// the other LDS buffer while the current one is multiplied (one barrier per tile).
+template <bool TA, bool TB, int EPI, int NL, bool FAST>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
+  constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
   constexpr int BT = 64 * NL, kLd = BT + 4, WT = 32 * NL;   // block tile, LDS row stride, wave tile
-  constexpr int kBM = BT, kBN = BT;
-  __shared__ __attribute__((aligned(16))) float As[kBK][kLd];
-  __shared__ __attribute__((aligned(16))) float Bs[kBK][kLd];
+  constexpr int kBM = BT, kBN = BT, NV = NL * BK / 16;
+  __shared__ __attribute__((aligned(16))) float As[NBUF][BK][kLd];
+  __shared__ __attribute__((aligned(16))) float Bs[NBUF][BK][kLd];
   const float* A = g.A + (int64_t)blockIdx.z * g.sA;
   const float* B = g.B + (int64_t)blockIdx.z * g.sB;
   float* C = g.C + (int64_t)blockIdx.z * g.sC;
@@ -136,32 +199,44 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  float4 ra[NL], rb[NL];
+  float4 ra[NV], rb[NV];
+  FastLoader<NL, BK, !TA> fa;   // A is [M][K] (row-major in M) unless TA
+  FastLoader<NL, BK, TB> fb;    // B is [N][K] only if TB
+  if (FAST) {
+    fa.init(A, g.lda, g.K, g.M, m0);
+    fb.init(B, g.ldb, g.K, g.N, n0);
+  }
   auto fetch = [&](int k0) {
-    if (TA) load_direct<NL>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    else load_transposed<NL>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    if (TB) load_transposed<NL>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
-    else load_direct<NL>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    if (FAST) {
+      fa.load(k0 / BK, ra);
+      fb.load(k0 / BK, rb);
+      return;
+    }
+    if (TA) load_direct<NL, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    else load_transposed<NL, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    if (TB) load_transposed<NL, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    else load_direct<NL, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
   };
-  auto stage = [&]() {
-    if (TA) store_direct<NL>(As, ra); else store_transposed<NL>(As, ra);
-    if (TB) store_transposed<NL>(Bs, rb); else store_direct<NL>(Bs, rb);
+  auto stage = [&](int buf) {
+    if (TA) store_direct<NL, BK>(As[buf], ra); else store_transposed<NL, BK>(As[buf], ra);
+    if (TB) store_transposed<NL, BK>(Bs[buf], rb); else store_direct<NL, BK>(Bs[buf], rb);
   };
 
   fetch(0);
-  stage();
+  stage(0);
   __syncthreads();
   const int kh = lane >> 5, li = lane & 31;
-  for (int k0 = 0; k0 < g.K; k0 += kBK) {
-    const bool more = k0 + kBK < g.K;
-    if (more) fetch(k0 + kBK);
+  int cur = 0;
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+    const bool more = k0 + BK < g.K;
+    if (more) fetch(k0 + BK);
 #pragma unroll
-    for (int kk = 0; kk < kBK; kk += 2) {
+    for (int kk = 0; kk < BK; kk += 2) {
       float av[NL], bv[NL];
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        av[i] = As[kk + kh][wy * WT + 32 * i + li];
-        bv[i] = Bs[kk + kh][wx * WT + 32 * i + li];
+        av[i] = As[cur][kk + kh][wy * WT + 32 * i + li];
+        bv[i] = Bs[cur][kk + kh][wx * WT + 32 * i + li];
       }
 #pragma unroll
       for (int i = 0; i < NL; ++i)
@@ -169,10 +244,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
         for (int j = 0; j < NL; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
-    if (more) {
-      stage();
+    if (NBUF == 2) {
+      // the other buffer was last read before the previous barrier: free to overwrite
+      if (more) stage(cur ^ 1);
       __syncthreads();
+      cur ^= 1;
+    } else {
+      __syncthreads();
+      if (more) {
+        stage(0);
+        __syncthreads();
+      }
     }
   }
 
@@ -211,7 +293,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
       const uint32_t o = (uint32_t)__shfl_xor((int)dmax, off);
       dmax = dmax > o ? dmax : o;
     }
-    uint32_t* red = reinterpret_cast<uint32_t*>(&As[0][0]);
+    uint32_t* red = reinterpret_cast<uint32_t*>(&As[0][0][0]);
     if (lane == 0) red[wave] = dmax;
     __syncthreads();
     if (threadIdx.x == 0)
@@ -469,8 +551,15 @@ template <bool TA, bool TB, int EPI>
 static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch) {
   const int bt = gemm_tile(ctx, g.M, g.N, batch);
   const dim3 grid((unsigned)((g.N + bt - 1) / bt), (unsigned)((g.M + bt - 1) / bt), (unsigned)batch);
-  if (bt == 128) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2>), grid, dim3(kThreads), 0, ctx->stream, g);
-  else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1>), grid, dim3(kThreads), 0, ctx->stream, g);
+  // fast loaders need aligned operand rows and no float4 straddling an operand edge
+  const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4;
+  if (bt == 128) {
+    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), grid, dim3(kThreads), 0, ctx->stream, g);
+    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, false>), grid, dim3(kThreads), 0, ctx->stream, g);
+  } else {
+    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, true>), grid, dim3(kThreads), 0, ctx->stream, g);
+    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, false>), grid, dim3(kThreads), 0, ctx->stream, g);
+  }
 }
 
 static inline int vec_ok(const void* p, int64_t ld) { return (((uintptr_t)p & 15) == 0 && (ld & 3) == 0) ? 1 : 0; }

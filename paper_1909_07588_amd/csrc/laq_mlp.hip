@@ -182,8 +182,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
   constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
   constexpr int BT = 64 * NL, kLd = BT + 4, WT = 32 * NL;   // block tile, LDS row stride, wave tile
   constexpr int kBM = BT, kBN = BT, NV = NL * BK / 16;
-  __shared__ __attribute__((aligned(16))) float As[NBUF][BK][kLd];
-  __shared__ __attribute__((aligned(16))) float Bs[NBUF][BK][kLd];
+  extern __shared__ __attribute__((aligned(16))) float gemm_smem[];
+  float (*As)[BK][kLd] = reinterpret_cast<float (*)[BK][kLd]>(gemm_smem);
+  float (*Bs)[BK][kLd] = reinterpret_cast<float (*)[BK][kLd]>(gemm_smem + NBUF * BK * kLd);
   const float* A = g.A + (int64_t)blockIdx.z * g.sA;
   const float* B = g.B + (int64_t)blockIdx.z * g.sB;
   float* C = g.C + (int64_t)blockIdx.z * g.sC;
@@ -547,18 +548,23 @@ size_t mlp_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
   return (size_t)make_plan(ctx, N_m).total_floats * sizeof(float) + 256;
 }
 
+static size_t gemm_lds_bytes(int bt) {
+  return (size_t)2 * LAQ_GEMM_NBUF * LAQ_GEMM_BK * (bt + 4) * sizeof(float);
+}
+
 template <bool TA, bool TB, int EPI>
 static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch) {
   const int bt = gemm_tile(ctx, g.M, g.N, batch);
   const dim3 grid((unsigned)((g.N + bt - 1) / bt), (unsigned)((g.M + bt - 1) / bt), (unsigned)batch);
   // fast loaders need aligned operand rows and no float4 straddling an operand edge
   const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4;
+  const size_t smem = gemm_lds_bytes(bt);
   if (bt == 128) {
-    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), grid, dim3(kThreads), 0, ctx->stream, g);
-    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, false>), grid, dim3(kThreads), 0, ctx->stream, g);
+    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), grid, dim3(kThreads), smem, ctx->stream, g);
+    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, false>), grid, dim3(kThreads), smem, ctx->stream, g);
   } else {
-    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, true>), grid, dim3(kThreads), 0, ctx->stream, g);
-    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, false>), grid, dim3(kThreads), 0, ctx->stream, g);
+    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, true>), grid, dim3(kThreads), smem, ctx->stream, g);
+    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, false>), grid, dim3(kThreads), smem, ctx->stream, g);
   }
 }
 

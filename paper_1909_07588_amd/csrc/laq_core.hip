@@ -402,8 +402,12 @@ struct ServerArgs {
   DeviceScalars sc;
   int64_t p, p_stride, w_stride;
   int32_t M, D, b, J;
+  int32_t fused_finish;   // 1: the last block to finish does the bookkeeping (small grids)
   float alpha;
 };
+
+template <int B>
+__device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks);
 
 constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
 
@@ -423,20 +427,30 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   __shared__ int n_up_s;
 
   // ascending list of workers whose message carries a non-zero innovation
-  for (int m = threadIdx.x; m < a.M; m += kThreads) {
-    const float R = a.R_in[m];
-    const QuantConst c = quant_const<B>(__float_as_uint(R));
-    Rm[m] = R;
-    stepm[m] = (a.upload[m] && !c.zero) ? c.step : -1.0f;
+  // (order-preserving compaction: wavefront ballots + prefix counts)
+  __shared__ int wave_cnt[kThreads / 64];
+  if (threadIdx.x == 0) n_up_s = 0;
+  for (int base = 0; base < a.M; base += kThreads) {
+    const int m = base + threadIdx.x;
+    bool on = false;
+    if (m < a.M) {
+      const float R = a.R_in[m];
+      const QuantConst c = quant_const<B>(__float_as_uint(R));
+      Rm[m] = R;
+      on = a.upload[m] && !c.zero;
+      stepm[m] = on ? c.step : -1.0f;
+    }
+    const unsigned long long bal = __ballot(on);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int before = n_up_s;
+    for (int wv = 0; wv < wave; ++wv) before += wave_cnt[wv];
+    if (on) list[before + __popcll(bal & ((1ull << lane) - 1ull))] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) n_up_s += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    __syncthreads();
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int n = 0;
-    for (int m = 0; m < a.M; ++m)
-      if (stepm[m] >= 0.0f) list[n++] = m;
-    n_up_s = n;
-  }
-  __syncthreads();
   const int n_up = n_up_s;
 
   const int64_t nfull = a.p / kGroup;
@@ -523,20 +537,30 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   }
 
   n2 = wave_sum_f64(n2);
-  __shared__ double smd[kThreads];
+  __shared__ double smd[kThreads / 64];
   __shared__ bool last_s;
   if ((threadIdx.x & 63) == 0) smd[threadIdx.x >> 6] = n2;
   __syncthreads();
   if (threadIdx.x == 0) {
     a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
-    __threadfence();
-    last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
+    if (a.fused_finish) {
+      __threadfence();
+      last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
+    }
   }
+  if (!a.fused_finish) return;      // large grids: a follow-up kernel finishes (no fences here)
   __syncthreads();
   if (!last_s) return;
   __threadfence();
+  if (threadIdx.x == 0) *a.sc.srv_ticket = 0;
+  server_finish<B>(a, (int)gridDim.x);
+}
 
-  // last block: bookkeeping of Algorithm 2 and the parameter-difference history
+// Bookkeeping of Algorithm 2 (clocks, error norms, counters) and the new entry
+// alpha^2 ||nabla||^2 of the parameter-difference history; run by one block.
+template <int B>
+__device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks) {
+  __shared__ double red[kThreads];
   unsigned long long my_bits = 0;
   for (int m = threadIdx.x; m < a.M; m += kThreads) {
     if (a.upload[m]) {
@@ -551,19 +575,23 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   if (my_bits) atomicAdd(a.sc.bits, my_bits);
   // ||nabla||^2: block partials summed in a fixed order (strided, then a tree)
   double tot = 0.0;
-  for (unsigned i = threadIdx.x; i < gridDim.x; i += kThreads)
+  for (int i = threadIdx.x; i < n_blocks; i += kThreads)
     tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  smd[threadIdx.x] = tot;
+  red[threadIdx.x] = tot;
   __syncthreads();
   for (int off = kThreads / 2; off > 0; off >>= 1) {
-    if ((int)threadIdx.x < off) smd[threadIdx.x] += smd[threadIdx.x + off];
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
   if (threadIdx.x == 0) {
     for (int d = a.D - 1; d > 0; --d) a.sc.dtheta2[d] = a.sc.dtheta2[d - 1];
-    a.sc.dtheta2[0] = ((double)a.alpha * (double)a.alpha) * smd[0];
-    *a.sc.srv_ticket = 0;
+    a.sc.dtheta2[0] = ((double)a.alpha * (double)a.alpha) * red[0];
   }
+}
+
+template <int B>
+__global__ __launch_bounds__(kThreads) void server_finish_kernel(ServerArgs a, int n_blocks) {
+  server_finish<B>(a, n_blocks);
 }
 
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
@@ -662,6 +690,8 @@ static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
 template <int B>
 static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArgs& a) {
   hipLaunchKernelGGL(server_kernel<B>, grid, dim3(kThreads), smem, s, a);
+  if (!a.fused_finish)
+    hipLaunchKernelGGL(server_finish_kernel<B>, dim3(1), dim3(kThreads), 0, s, a, (int)grid.x);
 }
 
 #define LAQ_DISPATCH_B(b, CALL)                                                                   \
@@ -837,6 +867,7 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
   a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
   a.M = ctx->M; a.D = ctx->D; a.b = ctx->b; a.alpha = ctx->alpha;
   const int64_t blocks = server_blocks(ctx->p, &a.J);
+  a.fused_finish = blocks <= 64;
   const size_t smem = (size_t)ctx->M * 12;
   const dim3 grid((unsigned)blocks);
 #define LAQ_CALL(BB) launch_server<BB>(grid, smem, ctx->stream, a)

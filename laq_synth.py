@@ -122,6 +122,13 @@ def model_inputs(w):
     raise ValueError("workload has no model")
 
 
+def minibatch_indices(w, B, iteration):
+    """Sample indices idx[M][B] (int32, into each worker's own shard, without repeats inside
+    a batch) for one stochastic iteration; a function of (workload, B, iteration) only."""
+    rng = _rng(w.cfg, stream=1000 + iteration)
+    return np.stack([rng.permutation(w.N_m)[:B] for _ in range(w.M)]).astype(np.int32)
+
+
 def worker_scales(M, cfg=4):
     """s_m log-uniform in [1e-3, 1]."""
     u = _rng(cfg, 1).random(M)

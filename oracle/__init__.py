@@ -86,6 +86,9 @@ def _declare(L):
     L.laq_oracle_mlp_params.argtypes = [pi32, i32]
     L.laq_oracle_grads_all.restype = f64
     L.laq_oracle_grads_all.argtypes = [i32, pf, pf, pi32, i32, i64, i64, pi32, i32, f32, pf]
+    L.laq_oracle_grads_minibatch.restype = None
+    L.laq_oracle_grads_minibatch.argtypes = [i32, pf, pf, pi32, i32, i64, i64, pi32, i32, f32,
+                                             pi32, i64, pf]
 
 
 def _f32(a):
@@ -243,3 +246,23 @@ def grads_all(kind, theta, X, y, dims, lam):
                                       _p(y, C.c_int32), M, N_m, ldx, _p(d, C.c_int32), d.size,
                                       float(lam), _p(G, C.c_float))
     return G, loss
+
+
+def grads_minibatch(kind, theta, X, y, dims, lam, idx):
+    """Minibatch gradients of all workers (SLAQ): idx[M][B] int32 indices into each
+    worker's own shard.  Returns G[M][p]."""
+    X = _f32(X)
+    y = np.ascontiguousarray(y, np.int32)
+    theta = _f32(theta)
+    idx = np.ascontiguousarray(idx, np.int32)
+    M, N_m, ldx = X.shape
+    assert idx.shape[0] == M and idx.min() >= 0 and idx.max() < N_m
+    d = np.ascontiguousarray(dims, np.int32)
+    p = model_params(kind, dims)
+    assert theta.size == p
+    G = np.zeros((M, p), np.float32)
+    lib().laq_oracle_grads_minibatch(int(kind), _p(theta, C.c_float), _p(X, C.c_float),
+                                     _p(y, C.c_int32), M, N_m, ldx, _p(d, C.c_int32), d.size,
+                                     float(lam), _p(idx, C.c_int32), idx.shape[1],
+                                     _p(G, C.c_float))
+    return G

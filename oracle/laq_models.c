@@ -235,3 +235,32 @@ double laq_oracle_grads_all(int32_t kind, const float* theta, const float* X,
   free(loss);
   return tot / (double)N + 0.5 * (double)lambda * th2;
 }
+
+/* Minibatch gradients for the stochastic variant (Sec. 4, "Stochastic
+ * gradient-based tests": SLAQ is LAQ run on minibatch gradients).  Worker m
+ * draws B of its N_m samples, idx[m][0..B) (indices into its own shard, drawn
+ * by the caller), and returns the gradient of the loss its minibatch defines
+ * under the same mean convention:
+ *     g_m = (1/(M B)) sum_{j<B} grad CE_{idx[m][j]}(theta) + (1/M) lambda theta,
+ * an unbiased estimate of the full g_m = (1/N) sum_n grad CE_n + (N_m/N) lambda theta
+ * when the shards have equal size (N = M N_m).  Written as: copy the B drawn
+ * rows out, then take the full gradient of that B-sample shard with N = M B. */
+void laq_oracle_grads_minibatch(int32_t kind, const float* theta, const float* X,
+                                const int32_t* y, int32_t M, int64_t N_m,
+                                int64_t ldx, const int32_t* dims, int32_t n_dims,
+                                float lambda, const int32_t* idx, int64_t B,
+                                float* G) {
+  float* Xb = (float*)malloc((size_t)M * (size_t)B * (size_t)ldx * sizeof(float));
+  int32_t* yb = (int32_t*)malloc((size_t)M * (size_t)B * sizeof(int32_t));
+  for (int32_t m = 0; m < M; ++m) {
+    for (int64_t j = 0; j < B; ++j) {
+      const int64_t n = idx[(int64_t)m * B + j];
+      memcpy(Xb + ((int64_t)m * B + j) * ldx, X + ((int64_t)m * N_m + n) * ldx,
+             (size_t)ldx * sizeof(float));
+      yb[(int64_t)m * B + j] = y[(int64_t)m * N_m + n];
+    }
+  }
+  (void)laq_oracle_grads_all(kind, theta, Xb, yb, M, B, ldx, dims, n_dims, lambda, G);
+  free(Xb);
+  free(yb);
+}

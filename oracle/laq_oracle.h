@@ -147,6 +147,15 @@ double laq_oracle_grads_all(int32_t kind, const float* theta, const float* X,
                             int64_t ldx, const int32_t* dims, int32_t n_dims,
                             float lambda, float* G);
 
+/* Minibatch gradients (SLAQ, Sec. 4): worker m uses the B samples
+ * idx[m][0..B) of its shard; g_m = (1/(M B)) sum_j grad CE_{idx[m][j]} +
+ * (1/M) lambda theta.  idx is [M][B], values in [0, N_m). */
+void laq_oracle_grads_minibatch(int32_t kind, const float* theta, const float* X,
+                                const int32_t* y, int32_t M, int64_t N_m,
+                                int64_t ldx, const int32_t* dims, int32_t n_dims,
+                                float lambda, const int32_t* idx, int64_t B,
+                                float* G);
+
 #ifdef __cplusplus
 }
 #endif

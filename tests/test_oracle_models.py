@@ -105,6 +105,68 @@ def test_mlp_matches_autograd_at_a_wider_shape_with_sparse_inputs():
         assert np.abs(G[m] - ref).max() <= 2e-7 * np.abs(ref).max()
 
 
+# ---- minibatch gradients (SLAQ, Sec. 4 "Stochastic gradient-based tests") ----
+
+@pytest.mark.parametrize("kind", [1, 2, 3])
+def test_minibatch_gradient_matches_float64_autograd_of_the_minibatch_loss(kind):
+    """g_m = grad of (1/(M B)) sum_{j} CE_{idx[m][j]} + (1/M)(lambda/2)||theta||^2, written with
+    torch float64 ops on the rows picked out by idx (repeats allowed)."""
+    X, y, theta, dims = _tiny(kind, seed=2)
+    M, N_m, _ = X.shape
+    lam = 0.01
+    rng = np.random.default_rng(5)
+    B = 4
+    idx = rng.integers(0, N_m, (M, B)).astype(np.int32)
+    idx[0] = [3, 3, 0, 6]                                   # a repeated sample
+    G = oracle.grads_minibatch(kind, theta, X, y, dims, lam, idx)
+    th = torch.from_numpy(theta.astype(np.float64)).requires_grad_(True)
+    for m in range(M):
+        th.grad = None
+        xs = torch.from_numpy(X[m][idx[m]][:, :dims[0]].astype(np.float64))
+        ys = y[m][idx[m]]
+        if kind == 1:
+            ce = torch.nn.functional.softplus(-torch.from_numpy(ys.astype(np.float64)) * (xs @ th)).sum()
+        elif kind == 2:
+            ce = torch.nn.functional.cross_entropy(xs @ th.reshape(dims[1], dims[0]).T,
+                                                   torch.from_numpy(ys).long(), reduction="sum")
+        else:
+            a, off = xs, 0
+            for l in range(len(dims) - 1):
+                W = th[off:off + dims[l] * dims[l + 1]].reshape(dims[l], dims[l + 1])
+                off += dims[l] * dims[l + 1]
+                bb = th[off:off + dims[l + 1]]
+                off += dims[l + 1]
+                a = a @ W + bb
+                if l + 2 < len(dims):
+                    a = torch.relu(a)
+            ce = torch.nn.functional.cross_entropy(a, torch.from_numpy(ys).long(), reduction="sum")
+        (ce / (M * B) + (1.0 / M) * 0.5 * lam * (th ** 2).sum()).backward()
+        ref = th.grad.numpy()
+        assert np.abs(G[m] - ref).max() <= 2e-7 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("kind", [1, 2, 3])
+def test_minibatch_gradients_over_a_partition_average_to_the_full_gradient(kind):
+    """Unbiasedness: the minibatch gradients of disjoint batches that cover the shard
+    average to the worker's full gradient (equal shards)."""
+    rng = np.random.default_rng(7)
+    X, y, theta, dims = _tiny(kind, seed=3)
+    X, y = np.concatenate([X, X[:, :1]], 1), np.concatenate([y, y[:, :1]], 1)   # N_m = 8
+    M, N_m, _ = X.shape
+    lam = 0.01
+    full, _ = oracle.grads_all(kind, theta, X, y, dims, lam)
+    B = 2
+    perm = np.stack([rng.permutation(N_m) for _ in range(M)]).astype(np.int32)
+    acc = np.zeros(full.shape, np.float64)
+    for k in range(N_m // B):
+        acc += oracle.grads_minibatch(kind, theta, X, y, dims, lam, perm[:, k * B:(k + 1) * B])
+    mean = acc / (N_m // B)
+    assert np.abs(mean - full).max() <= 1e-6 * np.abs(full).max()
+    # and a batch that is the whole shard, in any order, is the full gradient
+    whole = oracle.grads_minibatch(kind, theta, X, y, dims, lam, perm)
+    assert np.abs(whole - full).max() <= 1e-6 * np.abs(full).max()
+
+
 def test_parameter_counts():
     assert oracle.mlp_params((784, 200, 10)) == 159010
     assert oracle.mlp_params((784, 2048, 2048, 10)) == 5824522

@@ -48,8 +48,10 @@ def _traffic_table():
     return {}
 
 
-def run_model_workload(w, steps, warmup, phase_steps=100):
-    """Whole-loop rate and per-phase times of a model workload (cfg 1, 2, 3, 5)."""
+def run_model_workload(w, steps, warmup, phase_steps=100, minibatch=0):
+    """Whole-loop rate and per-phase times of a model workload (cfg 1, 2, 3, 5).  minibatch = B > 0
+    runs the stochastic variant: every iteration's gradients come from B drawn samples per worker
+    (64 index sets, drawn beforehand and resident on the device, used in turn)."""
     import torch
     import laq_synth
     import paper_1909_07588_amd as laq
@@ -62,9 +64,19 @@ def run_model_workload(w, steps, warmup, phase_steps=100):
     theta = torch.from_numpy(theta0.copy()).to(dev)
     G = ctx.alloc_G()
     codes, R, up = ctx.alloc_messages()
+    idx_sets = [torch.from_numpy(laq_synth.minibatch_indices(w, minibatch, i)).to(dev)
+                for i in range(64)] if minibatch else []
+    count = [0]
+
+    def grads():
+        if minibatch:
+            ctx.laq_worker_grads_minibatch(theta, idx_sets[count[0] % 64], G)
+            count[0] += 1
+        else:
+            ctx.laq_worker_grads(theta, G)
 
     def step():
-        ctx.laq_worker_grads(theta, G)
+        grads()
         ctx.laq_quantize_skip(G, codes, R, up)
         ctx.laq_server_step(codes, R, up, theta)
 
@@ -86,7 +98,7 @@ def run_model_workload(w, steps, warmup, phase_steps=100):
     ev = [_events(torch, 4) for _ in range(n)]
     for i in range(n):
         ev[i][0].record()
-        ctx.laq_worker_grads(theta, G)
+        grads()
         ev[i][1].record()
         ctx.laq_quantize_skip(G, codes, R, up)
         ev[i][2].record()
@@ -96,7 +108,8 @@ def run_model_workload(w, steps, warmup, phase_steps=100):
     ph = [sum(e[k].elapsed_time(e[k + 1]) for e in ev) / n for k in range(3)]
     it_total = warmup + steps
     res = {
-        "workload": w.name, "M": w.M, "N_m": w.N_m, "p": w.p, "b": w.b, "steps": steps,
+        "workload": w.name + (f"_slaq_B{minibatch}" if minibatch else ""), "M": w.M, "N_m": w.N_m, "p": w.p,
+        "b": w.b, "steps": steps,
         "iterations_per_s": round(steps / (total_ms * 1e-3), 2), "ms_per_step": round(total_ms / steps, 5),
         "phase_ms": {"worker_grads": round(ph[0], 5), "quantize_skip": round(ph[1], 5),
                      "server_step": round(ph[2], 5)},
@@ -271,6 +284,11 @@ def main():
             r, p3 = run_model_workload(wk, k, wu, phase_steps=min(k, 50))
             workloads.append(dict(r, rooflines=model_rooflines(wk, p3, traffic)))
             torch.cuda.empty_cache()
+        # stochastic variant on the headline shapes (Sec. 4: minibatch 500, alpha = 0.008, b = 3)
+        ws = laq_synth.workload(2)
+        ws.alpha = 0.008
+        r, _ = run_model_workload(ws, 500, 10, phase_steps=100, minibatch=500)
+        workloads.append(r)
         for b in (2, 4, 8):
             r, (alg_q, tq, alg_s, ts) = run_stress(b, 50, 3)
             name = r["workload"]

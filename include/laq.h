@@ -138,6 +138,23 @@ int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t
 int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev);
 
 /*
+ * Stochastic variant (Sec. 4, "Stochastic gradient-based tests": SLAQ is LAQ
+ * run on minibatch gradients).  idx_dev[M][B] int32 (device): worker m uses
+ * the B samples idx[m][0..B) of its own shard, indices in [0, N_m), drawn by
+ * the caller.  G_dev[m] = (1/(M B)) sum_j grad CE_{idx[m][j]}(theta)
+ * + (1/M) lambda theta: the gradient of the loss the minibatches define, an
+ * unbiased estimate of the full-batch g_m.  ws_dev: caller-owned scratch of
+ * laq_minibatch_workspace_bytes(ctx, B) bytes, 256-byte aligned (gathered
+ * rows and the model's scratch for B samples); the data bound by laq_set_data
+ * stays bound.  An index outside the shard is clamped and makes
+ * laq_get_counters return LAQ_EINVAL.  The radius hand-over to
+ * laq_quantize_skip works as for laq_worker_grads.
+ */
+size_t laq_minibatch_workspace_bytes(const laq_ctx* ctx, int64_t B);
+int laq_worker_grads_minibatch(laq_ctx* ctx, const float* theta_dev, const int32_t* idx_dev,
+                               int64_t B, void* ws_dev, size_t ws_bytes, float* G_dev);
+
+/*
  * Innovation quantizer (Sec. 2.1, eqs. 5-6) and skip rule (Sec. 2.2, eqs.
  * 7a-7b) for all workers.  With h_m the stored quantized gradient, L = 2^b-1,
  * and (+),(-),(*),(/) single binary32 operations:
@@ -189,7 +206,7 @@ typedef struct laq_state_view {
   double* rhs_dev;         /* [M] last call's right side of (7a)               */
   uint64_t* uploads_dev;   /* [M] upload counts                                */
   uint64_t* bits_dev;      /* [1] total transmitted bits                       */
-  uint32_t* status_dev;    /* [1] nonzero once a radius was not finite         */
+  uint32_t* status_dev;    /* [1] bit 0: a radius was not finite; bit 1: bad index */
   int64_t p_stride;
   int64_t w_stride;
 } laq_state_view;
@@ -198,7 +215,7 @@ int laq_get_state(laq_ctx* ctx, laq_state_view* view);
 
 /* Synchronises the stream and copies the counters to host arrays
  * uploads[M], *bits_total.  Returns LAQ_ENONFINITE if any radius so far was
- * not finite. */
+ * not finite, LAQ_EINVAL if a minibatch index was out of range. */
 int laq_get_counters(laq_ctx* ctx, uint64_t* uploads, uint64_t* bits_total);
 
 /* Text of the last error on this context ("" if none); owned by the context. */

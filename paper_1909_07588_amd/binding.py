@@ -13,7 +13,8 @@ MODE_FORCE_UPLOAD = 1
 
 EXPORTS = ["laq_p_stride", "laq_w_stride", "laq_workspace_bytes", "laq_create", "laq_destroy",
            "laq_reset", "laq_set_mode", "laq_set_model", "laq_model_workspace_bytes",
-           "laq_set_data", "laq_worker_grads", "laq_quantize_skip", "laq_server_step",
+           "laq_set_data", "laq_worker_grads", "laq_minibatch_workspace_bytes",
+           "laq_worker_grads_minibatch", "laq_quantize_skip", "laq_server_step",
            "laq_get_state", "laq_get_counters", "laq_last_error"]
 
 
@@ -67,6 +68,10 @@ def lib():
         L.laq_set_data.argtypes = [vp, vp, vp, i64, i64, vp, sz]
         L.laq_worker_grads.restype = C.c_int
         L.laq_worker_grads.argtypes = [vp, vp, vp]
+        L.laq_minibatch_workspace_bytes.restype = sz
+        L.laq_minibatch_workspace_bytes.argtypes = [vp, i64]
+        L.laq_worker_grads_minibatch.restype = C.c_int
+        L.laq_worker_grads_minibatch.argtypes = [vp, vp, vp, i64, vp, sz, vp]
         L.laq_quantize_skip.restype = C.c_int
         L.laq_quantize_skip.argtypes = [vp, vp, vp, vp, vp]
         L.laq_server_step.restype = C.c_int
@@ -207,6 +212,21 @@ class Laq:
     def laq_worker_grads(self, theta, G):
         self._chk(self.L.laq_worker_grads(self.h, C.c_void_p(theta.data_ptr()), C.c_void_p(G.data_ptr())))
 
+    def laq_worker_grads_minibatch(self, theta, idx, G):
+        """idx[M][B] int32 device tensor of sample indices into each worker's shard."""
+        torch = self.torch
+        assert idx.dtype == torch.int32 and idx.is_contiguous() and idx.shape[0] == self.M
+        B = int(idx.shape[1])
+        need = int(self.L.laq_minibatch_workspace_bytes(self.h, B))
+        ws = getattr(self, "_mb_ws", None)
+        if ws is None or ws.numel() < need + 256:
+            ws = self._mb_ws = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        off = (-ws.data_ptr()) % 256
+        self._chk(self.L.laq_worker_grads_minibatch(self.h, C.c_void_p(theta.data_ptr()),
+                                                    C.c_void_p(idx.data_ptr()), B,
+                                                    C.c_void_p(ws.data_ptr() + off), need,
+                                                    C.c_void_p(G.data_ptr())))
+
     def laq_quantize_skip(self, G, codes, R, upload):
         self._chk(self.L.laq_quantize_skip(self.h, C.c_void_p(G.data_ptr()), C.c_void_p(codes.data_ptr()),
                                            C.c_void_p(R.data_ptr()), C.c_void_p(upload.data_ptr())))
@@ -219,6 +239,6 @@ class Laq:
         up = (C.c_uint64 * self.M)()
         bits = C.c_uint64(0)
         st = self.L.laq_get_counters(self.h, up, C.byref(bits))
-        if st not in (OK, ENONFINITE):
+        if st not in (OK, ENONFINITE, EINVAL):
             self._chk(st)
         return np.array(list(up), np.uint64), int(bits.value), st

@@ -705,6 +705,44 @@ static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArg
     default: break;                                                                               \
   }
 
+// Minibatch rows of every worker, copied out of the resident shards:
+// Xb[m][j][:] = X[m][idx[m][j]][:], yb[m][j] = y[m][idx[m][j]].  One float4 per
+// thread.  An index outside [0, N_m) is clamped (no access leaves the shard)
+// and reported through the status word.
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(
+    const float* __restrict__ X, const int32_t* __restrict__ y, const int32_t* __restrict__ idx,
+    int64_t N_m, int64_t ldx, int64_t B, float* __restrict__ Xb, int32_t* __restrict__ yb,
+    uint32_t* __restrict__ status) {
+  const int m = blockIdx.y;
+  const int64_t nf4 = ldx >> 2;
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= B * nf4) return;
+  const int64_t j = i / nf4, c4 = i - j * nf4;
+  int64_t n = idx[(int64_t)m * B + j];
+  if (n < 0 || n >= N_m) {
+    if (c4 == 0) atomicOr(status, 2u);
+    n = n < 0 ? 0 : N_m - 1;
+  }
+  const float4 v = *reinterpret_cast<const float4*>(X + ((int64_t)m * N_m + n) * ldx + 4 * c4);
+  *reinterpret_cast<float4*>(Xb + ((int64_t)m * B + j) * ldx + 4 * c4) = v;
+  if (c4 == 0) yb[(int64_t)m * B + j] = y[(int64_t)m * N_m + n];
+}
+
+// layout of the minibatch workspace: gathered rows, gathered labels, model scratch for B samples
+struct MinibatchLayout {
+  size_t Xb, yb, model, total;
+};
+static MinibatchLayout minibatch_layout(const laq_ctx* ctx, int64_t B) {
+  MinibatchLayout l{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 255) & ~(size_t)255; return at; };
+  l.Xb = take((size_t)ctx->M * (size_t)B * (size_t)ctx->ldx * sizeof(float));
+  l.yb = take((size_t)ctx->M * (size_t)B * sizeof(int32_t));
+  l.model = take(model_workspace_bytes(ctx, B));
+  l.total = off;
+  return l;
+}
+
 }  // namespace laq
 
 using namespace laq;
@@ -906,6 +944,7 @@ int laq_get_counters(laq_ctx* ctx, uint64_t* uploads, uint64_t* bits_total) {
     LAQ_HIP(ctx, hipMemcpyAsync(bits_total, ctx->sc.bits, 8, hipMemcpyDeviceToHost, ctx->stream));
   LAQ_HIP(ctx, hipMemcpyAsync(&status, ctx->sc.status, 4, hipMemcpyDeviceToHost, ctx->stream));
   LAQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (status & 2u) return set_error(ctx, LAQ_EINVAL, "a minibatch index was outside its worker's shard");
   if (status) return set_error(ctx, LAQ_ENONFINITE, "a quantization radius was not finite");
   return LAQ_OK;
 }
@@ -984,6 +1023,42 @@ int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev) {
     }
     ctx->radius_for = G_dev;
   }
+  return st;
+}
+
+size_t laq_minibatch_workspace_bytes(const laq_ctx* ctx, int64_t B) {
+  if (!ctx || B < 1 || ctx->kind == LAQ_MODEL_NONE || !ctx->X) return 0;
+  return minibatch_layout(ctx, B).total;
+}
+
+int laq_worker_grads_minibatch(laq_ctx* ctx, const float* theta_dev, const int32_t* idx_dev, int64_t B,
+                               void* ws_dev, size_t ws_bytes, float* G_dev) {
+  if (!ctx) return LAQ_EINVAL;
+  if (ctx->kind == LAQ_MODEL_NONE || !ctx->X)
+    return set_error(ctx, LAQ_ESTATE, "laq_worker_grads_minibatch needs laq_set_model and laq_set_data");
+  if (!theta_dev || !G_dev || !idx_dev || (((uintptr_t)theta_dev | (uintptr_t)G_dev) & 15))
+    return set_error(ctx, LAQ_EINVAL, "laq_worker_grads_minibatch: null or misaligned pointer");
+  if (B < 1 || B > ctx->N_m)
+    return set_error(ctx, LAQ_EINVAL, "laq_worker_grads_minibatch: B = %lld outside 1..N_m", (long long)B);
+  const MinibatchLayout l = minibatch_layout(ctx, B);
+  if (!ws_dev || ws_bytes < l.total || ((uintptr_t)ws_dev & 255))
+    return set_error(ctx, LAQ_EINVAL, "laq_worker_grads_minibatch: workspace too small or misaligned (need %zu bytes)",
+                     l.total);
+  uint8_t* ws = static_cast<uint8_t*>(ws_dev);
+  float* Xb = reinterpret_cast<float*>(ws + l.Xb);
+  int32_t* yb = reinterpret_cast<int32_t*>(ws + l.yb);
+  const int64_t work = B * (ctx->ldx >> 2);
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((work + kThreads - 1) / kThreads), (unsigned)ctx->M),
+                     dim3(kThreads), 0, ctx->stream, ctx->X, ctx->y, idx_dev, ctx->N_m, ctx->ldx, B, Xb, yb,
+                     ctx->sc.status);
+  LAQ_HIP(ctx, hipGetLastError());
+  // the gradient of the loss the minibatch defines: the same kernels on the gathered rows
+  const float* X0 = ctx->X; const int32_t* y0 = ctx->y; const int64_t N0 = ctx->N_m;
+  uint8_t* mw0 = ctx->model_ws; const size_t mb0 = ctx->model_ws_bytes;
+  ctx->X = Xb; ctx->y = yb; ctx->N_m = B;
+  ctx->model_ws = ws + l.model; ctx->model_ws_bytes = l.total - l.model;
+  const int st = laq_worker_grads(ctx, theta_dev, G_dev);
+  ctx->X = X0; ctx->y = y0; ctx->N_m = N0; ctx->model_ws = mw0; ctx->model_ws_bytes = mb0;
   return st;
 }
 

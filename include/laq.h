@@ -62,6 +62,14 @@ typedef enum laq_model_kind {
 #define LAQ_MODE_FORCE_UPLOAD 1u /* every worker uploads every round: Algorithm 1 (QGD) */
 
 #define LAQ_MAX_BITS 16
+/* b = LAQ_B_EXACT selects the identity quantizer Q_m(theta^k) = grad f_m(theta^k): the limit of
+ * many bits, in which the skip rule (7a) has eps = 0 and LAQ becomes lazy aggregation of exact
+ * gradients (LAG); with LAQ_MODE_FORCE_UPLOAD it is plain gradient descent (eq. 2).  The message
+ * is g_m itself: codes_dev rows hold its p binary32 words (row stride laq_w_stride(p, 32)), an
+ * upload counts 32 p bits, R_dev still reports max |g - h|, and the left side of (7a) is
+ * ||g_m - h_m||^2 accumulated in binary64 in a fixed order (exact squares; unlike the integer
+ * sums of the b-bit path its last bits depend on that order). */
+#define LAQ_B_EXACT 32
 #define LAQ_MAX_LAYERS 8
 
 /* Row stride, in floats, of per-worker gradient matrices (p rounded up to a
@@ -80,7 +88,7 @@ size_t laq_workspace_bytes(int32_t M, int64_t p, int32_t b, int32_t D);
 
 /*
  * Algorithm 2, lines 1-2.  M workers, p parameters, b bits per coordinate
- * (1..16), D past parameter differences weighted by xi[0..D-1] (host array,
+ * (1..16, or LAQ_B_EXACT), D past parameter differences weighted by xi[0..D-1] (host array,
  * xi[d-1] = xi_d >= 0), clock limit t_bar >= D, step size alpha > 0.
  * workspace_dev: at least laq_workspace_bytes(M,p,b,D) bytes, 256-byte
  * aligned, owned by the caller.  hip_stream: a hipStream_t (NULL = the

@@ -5,4 +5,5 @@ of the path runs in the library's HIP kernels; torch provides device memory
 and the stream.  There is no CPU fallback: importing works without the
 library (so the package can be inspected), but any call fails loudly.
 """
-from .binding import Laq, LaqError, lib, lib_path, p_stride, w_stride  # noqa: F401
+from .binding import (B_EXACT, MODE_FORCE_UPLOAD, Laq, LaqError, lib, lib_path,  # noqa: F401
+                      p_stride, w_stride)

@@ -10,6 +10,7 @@ _LIB = os.path.join(_HERE, "liblaq_hip.so")
 OK, EINVAL, ESTATE, EDEVICE, ENONFINITE = 0, 1, 2, 3, 4
 MODEL_NONE, MODEL_BINLOG, MODEL_SOFTMAX, MODEL_MLP = 0, 1, 2, 3
 MODE_FORCE_UPLOAD = 1
+B_EXACT = 32          # laq_create's b for the identity quantizer (LAG / GD)
 
 EXPORTS = ["laq_p_stride", "laq_w_stride", "laq_workspace_bytes", "laq_create", "laq_destroy",
            "laq_reset", "laq_set_mode", "laq_set_model", "laq_model_workspace_bytes",

@@ -71,13 +71,22 @@ struct QuantConst {
   bool zero;    // zero (or unrepresentably small) innovation: all codes 0, delta 0
 };
 
+// B == kExact: the identity quantizer Q_m(theta^k) = grad f_m(theta^k), the limit of many
+// bits in which LAQ becomes lazy aggregation of exact gradients (remark after eqs. 7a-7b).
+constexpr int kExact = LAQ_B_EXACT;
+
 template <int B>
 __device__ __forceinline__ QuantConst quant_const(uint32_t rbits) {
   QuantConst c;
-  constexpr float Lf = (float)((1 << B) - 1);
   c.R = __uint_as_float(rbits);
   const float two_R = 2.0f * c.R;
   c.finite = (rbits < 0x7f800000u) && (abs_bits(two_R) < 0x7f800000u);
+  if constexpr (B == kExact) {
+    c.s = 0.0f; c.step = 0.0f; c.x = 0;
+    c.zero = !c.finite || c.R == 0.0f;
+    return c;
+  }
+  constexpr float Lf = (float)((1u << (B & 31)) - 1u);
   // binary64 quotient of two binary32 values, rounded once more to binary32,
   // equals the correctly rounded binary32 quotient (53 >= 2*24 + 2).
   c.s = (float)((double)Lf / (double)two_R);
@@ -181,6 +190,33 @@ struct QuantArgs {
   float alpha;
   uint32_t mode;
 };
+
+// The skip rule (eqs. 7a-7b) for worker m in binary64 with a fixed operation order, and the
+// per-call stash read by the server step; run by one thread.
+__device__ __forceinline__ void apply_skip_rule(const QuantArgs& a, int m, float R, bool finite, double lhs,
+                                                double E2, long long Sq) {
+  double Hsum = 0.0;
+  for (int d = 0; d < a.D; ++d) {
+    const double term = a.sc.xi[d] * a.sc.dtheta2[d];
+    Hsum = (d == 0) ? term : Hsum + term;
+  }
+  const double a2 = (double)a.alpha * (double)a.alpha;
+  const double m2 = (double)a.M * (double)a.M;
+  const double cc = 1.0 / (a2 * m2);
+  const double err = E2 + a.sc.Ehat2[m];
+  const double t1 = cc * Hsum;
+  const double t2 = 3.0 * err;
+  const double rhs = t1 + t2;
+  bool skip = (a.sc.t[m] < a.t_bar) && (lhs <= rhs);
+  if (a.mode & LAQ_MODE_FORCE_UPLOAD) skip = false;
+  if (!finite) { skip = true; atomicOr(a.sc.status, 1u); }
+  a.upload[m] = skip ? 0 : 1;
+  a.R_out[m] = R;
+  a.sc.Sq[m] = Sq;
+  a.sc.E2[m] = E2;
+  a.sc.lhs[m] = lhs;
+  a.sc.rhs[m] = rhs;
+}
 
 template <int B>
 __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t n_slots);
@@ -362,32 +398,91 @@ __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t
   const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
   const double r = (double)c.R / (double)L;
   const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
-  double Hsum = 0.0;
-  for (int d = 0; d < a.D; ++d) {
-    const double term = a.sc.xi[d] * a.sc.dtheta2[d];
-    Hsum = (d == 0) ? term : Hsum + term;
-  }
-  const double a2 = (double)a.alpha * (double)a.alpha;
-  const double m2 = (double)a.M * (double)a.M;
-  const double cc = 1.0 / (a2 * m2);
-  const double err = E2 + a.sc.Ehat2[m];
-  const double t1 = cc * Hsum;
-  const double t2 = 3.0 * err;
-  const double rhs = t1 + t2;
-  bool skip = (a.sc.t[m] < a.t_bar) && (lhs <= rhs);
-  if (a.mode & LAQ_MODE_FORCE_UPLOAD) skip = false;
-  if (!c.finite) { skip = true; atomicOr(a.sc.status, 1u); }
-  a.upload[m] = skip ? 0 : 1;
-  a.R_out[m] = c.R;
-  a.sc.Sq[m] = c.zero ? 0 : (long long)Sq;
-  a.sc.E2[m] = E2;
-  a.sc.lhs[m] = lhs;
-  a.sc.rhs[m] = rhs;
+  apply_skip_rule(a, m, c.R, c.finite, lhs, E2, c.zero ? 0 : (long long)Sq);
 }
 
 template <int B>
 __global__ __launch_bounds__(kThreads) void decide_kernel(QuantArgs a, int32_t n_slots) {
   decide_worker<B>(a, blockIdx.x, n_slots);
+}
+
+// ------------------------------------------------------------------ identity quantizer (b = LAQ_B_EXACT)
+//
+// One pass: the message of worker m is grad f_m itself (32 p bits), so nothing
+// depends on the radius; the pass copies g into the message buffer and leaves, per
+// block, max |g - h| and the binary64 sum of (g - h)^2 (each square is exact in
+// binary64; lanes add sequentially, then a wavefront tree, then the four waves).
+__global__ __launch_bounds__(kThreads) void exact_message_kernel(QuantArgs a) {
+  const int64_t nfull = a.p / kGroup;
+  const int64_t first = (int64_t)blockIdx.x * a.U * kThreads + threadIdx.x;
+  const int m = blockIdx.y;
+  const float* g = a.G + (int64_t)m * a.p_stride;
+  const float* h = a.H + (int64_t)m * a.p_stride;
+  float* out = reinterpret_cast<float*>(a.codes + (int64_t)m * a.w_stride);
+  uint32_t mx = 0;
+  double acc = 0.0;
+  for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads) {
+    const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
+    const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
+    const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
+    const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) {
+      const float d = gv[j] - hv[j];
+      mx = max(mx, abs_bits(d));
+      acc = fma((double)d, (double)d, acc);
+    }
+    float4* op = reinterpret_cast<float4*>(out + grp * kGroup);
+    op[0] = g0;
+    op[1] = g1;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int64_t i = nfull * kGroup;
+    for (; i < a.p; ++i) {
+      const float d = g[i] - h[i];
+      mx = max(mx, abs_bits(d));
+      acc = fma((double)d, (double)d, acc);
+      out[i] = g[i];
+    }
+    for (; i < a.w_stride; ++i) out[i] = 0.0f;
+  }
+  __shared__ uint32_t smR[kWavesPerBlock];
+  __shared__ double smD[kWavesPerBlock];
+  mx = wave_max_u32(mx);
+  acc = wave_sum_f64(acc);
+  if ((threadIdx.x & 63) == 0) { smR[threadIdx.x >> 6] = mx; smD[threadIdx.x >> 6] = acc; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int64_t slot = (int64_t)m * a.slots + blockIdx.x;
+    a.sc.Rpart[slot] = max(max(smR[0], smR[1]), max(smR[2], smR[3]));
+    a.sc.Npart[slot] = (unsigned long long)__double_as_longlong((smD[0] + smD[1]) + (smD[2] + smD[3]));
+  }
+}
+
+// ||g_m - h_m||^2 from the block partials (strided per thread, then a tree: a fixed order), the
+// radius, and the skip rule with eps = 0; one block per worker.
+__global__ __launch_bounds__(kThreads) void exact_decide_kernel(QuantArgs a, int32_t n_slots) {
+  __shared__ double red[kThreads];
+  __shared__ uint32_t smR[kWavesPerBlock];
+  const int m = blockIdx.x;
+  double tot = 0.0;
+  uint32_t rb = 0;
+  for (int i = threadIdx.x; i < n_slots; i += kThreads) {
+    tot += __longlong_as_double((long long)a.sc.Npart[(int64_t)m * a.slots + i]);
+    rb = max(rb, a.sc.Rpart[(int64_t)m * a.slots + i]);
+  }
+  red[threadIdx.x] = tot;
+  rb = wave_max_u32(rb);
+  if ((threadIdx.x & 63) == 0) smR[threadIdx.x >> 6] = rb;
+  __syncthreads();
+  for (int off = kThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x != 0) return;
+  const QuantConst c = quant_const<kExact>(max(max(smR[0], smR[1]), max(smR[2], smR[3])));
+  apply_skip_rule(a, m, c.R, c.finite, c.finite ? red[0] : 0.0, 0.0, 0);
 }
 
 // ------------------------------------------------------------------ server step
@@ -419,7 +514,7 @@ constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
 // ascending m -- the order in which the sums are defined.
 template <int B>
 __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
-  constexpr uint32_t L = (1u << B) - 1u;
+  constexpr uint32_t L = B >= 32 ? 0xffffffffu : (1u << (B & 31)) - 1u;
   extern __shared__ unsigned char smem_raw[];
   int32_t* list = reinterpret_cast<int32_t*>(smem_raw);           // [M] uploading workers, ascending
   float* Rm = reinterpret_cast<float*>(list + a.M);               // [M]
@@ -437,7 +532,7 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
       const float R = a.R_in[m];
       const QuantConst c = quant_const<B>(__float_as_uint(R));
       Rm[m] = R;
-      on = a.upload[m] && !c.zero;
+      on = a.upload[m] && (B == kExact || !c.zero);   // the exact message is stored even if it repeats h
       stepm[m] = on ? c.step : -1.0f;
     }
     const unsigned long long bal = __ballot(on);
@@ -471,17 +566,29 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
     for (int j = 0; j < kServerJ; ++j) {
       const int64_t grp = grp0 + j * span;
       if (j < a.J && grp < nfull) {
-        const unsigned __int128 v = load_group<B>(crow + grp * B);
         float4* hp = reinterpret_cast<float4*>(hrow + grp * kGroup);
         const float4 h0 = hp[0], h1 = hp[1];
         float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+        if constexpr (B == kExact) {
+          const float4* cp = reinterpret_cast<const float4*>(crow + grp * (int64_t)(kGroup * 4));
+          const float4 g0 = cp[0], g1 = cp[1];
+          const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
-        for (int i = 0; i < kGroup; ++i) {
-          const uint32_t q = (uint32_t)(v >> (i * B)) & L;
-          float dq = (float)q * step;
-          dq = dq - R;
-          hv[i] = hv[i] + dq;
-          acc[j][i] = acc[j][i] + dq;
+          for (int i = 0; i < kGroup; ++i) {
+            const float dq = gv[i] - hv[i];
+            hv[i] = gv[i];
+            acc[j][i] = acc[j][i] + dq;
+          }
+        } else {
+          const unsigned __int128 v = load_group<B>(crow + grp * B);
+#pragma unroll
+          for (int i = 0; i < kGroup; ++i) {
+            const uint32_t q = (uint32_t)(v >> (i * B)) & L;
+            float dq = (float)q * step;
+            dq = dq - R;
+            hv[i] = hv[i] + dq;
+            acc[j][i] = acc[j][i] + dq;
+          }
         }
         hp[0] = make_float4(hv[0], hv[1], hv[2], hv[3]);
         hp[1] = make_float4(hv[4], hv[5], hv[6], hv[7]);
@@ -519,13 +626,20 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
       for (int k = 0; k < n_up; ++k) {
         const int m = list[k];
         const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
-        const int64_t bit = i * B;
-        uint32_t q = 0;
-        for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
-        float dq = (float)q * stepm[m];
-        dq = dq - Rm[m];
         float* hp = a.H + (int64_t)m * a.p_stride + i;
-        *hp = *hp + dq;
+        float dq;
+        if constexpr (B == kExact) {
+          const float gval = reinterpret_cast<const float*>(row)[i];
+          dq = gval - *hp;
+          *hp = gval;
+        } else {
+          const int64_t bit = i * B;
+          uint32_t q = 0;
+          for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
+          dq = (float)q * stepm[m];
+          dq = dq - Rm[m];
+          *hp = *hp + dq;
+        }
         acc1 = acc1 + dq;
       }
       const float nb = a.nabla[i] + acc1;
@@ -567,7 +681,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks)
       a.sc.Ehat2[m] = a.sc.E2[m];
       a.sc.t[m] = 0;
       a.sc.uploads[m] += 1;
-      my_bits += 32ull + (unsigned long long)B * (unsigned long long)a.p;
+      my_bits += (B == kExact ? 0ull : 32ull) + (unsigned long long)B * (unsigned long long)a.p;
     } else {
       a.sc.t[m] += 1;
     }
@@ -674,7 +788,7 @@ static Layout make_layout(int32_t M, int64_t p, int32_t D) {
 }
 
 static bool valid_sizes(int32_t M, int64_t p, int32_t b, int32_t D) {
-  if (!(M >= 1 && M <= 65535 && p >= 1 && p < ((int64_t)1 << 31) && b >= 1 && b <= LAQ_MAX_BITS &&
+  if (!(M >= 1 && M <= 65535 && p >= 1 && p < ((int64_t)1 << 31) && ((b >= 1 && b <= LAQ_MAX_BITS) || b == LAQ_B_EXACT) &&
         D >= 1 && D <= 4096))
     return false;
   // every lane handles at most 512 groups of 8 coordinates per pass
@@ -870,6 +984,13 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   const dim3 grid((unsigned)sw.Gx, (unsigned)ctx->M);
   a.U = sw.U;
   a.fused_decide = sw.Gx <= 64;
+  if (ctx->b == LAQ_B_EXACT) {
+    hipLaunchKernelGGL(exact_message_kernel, grid, dim3(kThreads), 0, ctx->stream, a);
+    hipLaunchKernelGGL(exact_decide_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, a,
+                       (int32_t)sw.Gx);
+    LAQ_HIP(ctx, hipGetLastError());
+    return LAQ_OK;
+  }
   if (ctx->radius_for == G_dev && G_dev != nullptr) {
     // laq_worker_grads produced these gradients and left the block maxima of
     // |g - h| behind: the radius pass (a full read of g and h) is not needed
@@ -909,7 +1030,8 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
   const size_t smem = (size_t)ctx->M * 12;
   const dim3 grid((unsigned)blocks);
 #define LAQ_CALL(BB) launch_server<BB>(grid, smem, ctx->stream, a)
-  LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
+  if (ctx->b == LAQ_B_EXACT) LAQ_CALL(kExact);
+  else LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
 #undef LAQ_CALL
   LAQ_HIP(ctx, hipGetLastError());
   return LAQ_OK;

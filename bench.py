@@ -193,7 +193,8 @@ def run_stress(b, steps, warmup):
 def pmc_probe():
     """Short fixed sequence for counter collection under `rocprofv3 --pmc`: a 1 GiB device
     copy (calibrates FETCH_SIZE / WRITE_SIZE against a known size), three iterations of the
-    bandwidth-stress workload at b = 4, twenty iterations of the headline workload."""
+    bandwidth-stress workload at b = 4, twenty iterations of the headline workload, three of
+    the 784-2048-2048-10 network."""
     import torch
     import laq_synth
     import paper_1909_07588_amd as laq
@@ -217,7 +218,48 @@ def pmc_probe():
     ctx.close()
     del G
     run_model_workload(laq_synth.workload(2), 20, 2, phase_steps=1)
+    run_model_workload(laq_synth.workload(5), 1, 1, phase_steps=1)
     print("pmc probe done", flush=True)
+
+
+def modes_table(iters=500):
+    """Table-2-style rows on the headline shapes (synthetic data): the same kernels run as GD
+    (exact messages, every worker uploads), QGD (Algorithm 1: b-bit messages, every worker
+    uploads), LAG (exact messages, skip rule) and LAQ (Algorithm 2), for a fixed number of
+    iterations; uploads, transmitted bits and the final alpha^2 ||nabla||^2."""
+    import torch
+    import laq_synth
+    import paper_1909_07588_amd as laq
+    dev = "cuda:0"
+    w = laq_synth.workload(2)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    Xd, yd = torch.from_numpy(X).to(dev), torch.from_numpy(y).to(dev)
+    rows = []
+    for name, b, force in (("GD", laq.B_EXACT, True), ("QGD", w.b, True), ("LAG", laq.B_EXACT, False),
+                           ("LAQ", w.b, False)):
+        ctx = laq.Laq(w.M, w.p, b, w.D, w.xi, w.t_bar, w.alpha, device=dev)
+        if force:
+            ctx.laq_set_mode(laq.MODE_FORCE_UPLOAD)
+        ctx.laq_set_model(w.kind, w.dims, w.lam)
+        ctx.laq_set_data(Xd, yd)
+        theta = torch.from_numpy(theta0.copy()).to(dev)
+        G = ctx.alloc_G()
+        codes, R, up = ctx.alloc_messages()
+        e0, e1 = _events(torch, 2)
+        e0.record()
+        for _ in range(iters):
+            ctx.laq_worker_grads(theta, G)
+            ctx.laq_quantize_skip(G, codes, R, up)
+            ctx.laq_server_step(codes, R, up, theta)
+        e1.record()
+        torch.cuda.synchronize()
+        uploads, bits, status = ctx.laq_get_counters()
+        assert status == 0
+        rows.append({"mode": name, "b": int(b), "iterations": iters, "uploads": int(uploads.sum()),
+                     "bits": int(bits), "last_dtheta2": float(ctx.state()["dtheta2"][0].item()),
+                     "ms_per_iteration": round(e0.elapsed_time(e1) / iters, 5)})
+        ctx.close()
+    print(json.dumps({"workload": w.name, "alpha": w.alpha, "table": rows}), flush=True)
 
 
 def cpu_baseline(w, budget_s=12.0, max_iters=50):
@@ -252,6 +294,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 5], help="headline workload")
     ap.add_argument("--pmc-probe", action="store_true", help="short run for rocprofv3 --pmc (no timing)")
+    ap.add_argument("--modes-table", action="store_true",
+                    help="GD / QGD / LAG / LAQ on the headline shapes: uploads and bits after --steps iterations")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all M workers are simulated on one MI355X); "
@@ -267,6 +311,9 @@ def main():
         sys.exit(3)
     if args.pmc_probe:
         pmc_probe()
+        return
+    if args.modes_table:
+        modes_table(args.steps)
         return
     traffic = _traffic_table()
 

@@ -191,13 +191,22 @@ struct QuantArgs {
   uint32_t mode;
 };
 
+constexpr int kMaxHistLds = 256;   // history terms staged in LDS (longer histories fall back to global reads)
+
+// Stages xi_d * dtheta2[d] for d < min(D, kMaxHistLds) in LDS; every thread of the block calls it.
+__device__ __forceinline__ void stage_history(const QuantArgs& a, double* hterm) {
+  for (int d = threadIdx.x; d < a.D && d < kMaxHistLds; d += blockDim.x) hterm[d] = a.sc.xi[d] * a.sc.dtheta2[d];
+}
+
 // The skip rule (eqs. 7a-7b) for worker m in binary64 with a fixed operation order, and the
 // per-call stash read by the server step; run by one thread.
 __device__ __forceinline__ void apply_skip_rule(const QuantArgs& a, int m, float R, bool finite, double lhs,
-                                                double E2, long long Sq) {
+                                                double E2, long long Sq, const double* hterm) {
+  // hterm[d] = xi_d * ||theta^{k+1-d} - theta^{k-d}||^2, fetched by D threads at once (a loop of
+  // dependent global loads on one thread would cost a memory latency per term)
   double Hsum = 0.0;
   for (int d = 0; d < a.D; ++d) {
-    const double term = a.sc.xi[d] * a.sc.dtheta2[d];
+    const double term = d < kMaxHistLds ? hterm[d] : a.sc.xi[d] * a.sc.dtheta2[d];
     Hsum = (d == 0) ? term : Hsum + term;
   }
   const double a2 = (double)a.alpha * (double)a.alpha;
@@ -350,7 +359,7 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
       const int64_t slot = (int64_t)m * a.slots + blockIdx.x;
       a.sc.Spart[slot] = (smS[0] + smS[1]) + (smS[2] + smS[3]);
       a.sc.Npart[slot] = (smN[0] + smN[1]) + (smN[2] + smN[3]);
-      if (a.fused_decide) {
+      if (a.fused_decide && gridDim.x > 1) {
         // few blocks per worker: the last one to finish applies the skip rule
         // (saves a launch; with thousands of blocks the counter would serialise)
         __threadfence();
@@ -359,7 +368,9 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     }
     if (a.fused_decide) {
       __syncthreads();
-      if (last_s) {
+      if (gridDim.x == 1) {
+        decide_worker<B>(a, m, 1);            // one block per worker: its own partials, no hand-over
+      } else if (last_s) {
         __threadfence();
         if (threadIdx.x == 0) a.sc.ticket[m] = 0;
         decide_worker<B>(a, m, (int32_t)gridDim.x);
@@ -375,6 +386,8 @@ __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t
   constexpr int L = (1 << B) - 1;
   __shared__ unsigned long long smS[kThreads / 64], smN[kThreads / 64];
   __shared__ uint32_t smR[kThreads / 64];
+  __shared__ double hterm[kMaxHistLds];
+  stage_history(a, hterm);
   unsigned long long s64 = 0, n64 = 0;
   uint32_t rb = 0;
   for (int i = threadIdx.x; i < n_slots; i += kThreads) {
@@ -398,7 +411,7 @@ __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t
   const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
   const double r = (double)c.R / (double)L;
   const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
-  apply_skip_rule(a, m, c.R, c.finite, lhs, E2, c.zero ? 0 : (long long)Sq);
+  apply_skip_rule(a, m, c.R, c.finite, lhs, E2, c.zero ? 0 : (long long)Sq, hterm);
 }
 
 template <int B>
@@ -465,6 +478,8 @@ __global__ __launch_bounds__(kThreads) void exact_message_kernel(QuantArgs a) {
 __global__ __launch_bounds__(kThreads) void exact_decide_kernel(QuantArgs a, int32_t n_slots) {
   __shared__ double red[kThreads];
   __shared__ uint32_t smR[kWavesPerBlock];
+  __shared__ double hterm[kMaxHistLds];
+  stage_history(a, hterm);
   const int m = blockIdx.x;
   double tot = 0.0;
   uint32_t rb = 0;
@@ -482,7 +497,7 @@ __global__ __launch_bounds__(kThreads) void exact_decide_kernel(QuantArgs a, int
   }
   if (threadIdx.x != 0) return;
   const QuantConst c = quant_const<kExact>(max(max(smR[0], smR[1]), max(smR[2], smR[3])));
-  apply_skip_rule(a, m, c.R, c.finite, c.finite ? red[0] : 0.0, 0.0, 0);
+  apply_skip_rule(a, m, c.R, c.finite, c.finite ? red[0] : 0.0, 0.0, 0, hterm);
 }
 
 // ------------------------------------------------------------------ server step
@@ -657,16 +672,18 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   __syncthreads();
   if (threadIdx.x == 0) {
     a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
-    if (a.fused_finish) {
+    if (a.fused_finish && gridDim.x > 1) {
       __threadfence();
       last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
     }
   }
   if (!a.fused_finish) return;      // large grids: a follow-up kernel finishes (no fences here)
   __syncthreads();
-  if (!last_s) return;
-  __threadfence();
-  if (threadIdx.x == 0) *a.sc.srv_ticket = 0;
+  if (gridDim.x > 1) {
+    if (!last_s) return;
+    __threadfence();
+    if (threadIdx.x == 0) *a.sc.srv_ticket = 0;
+  }
   server_finish<B>(a, (int)gridDim.x);
 }
 
@@ -697,9 +714,16 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks)
     if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    for (int d = a.D - 1; d > 0; --d) a.sc.dtheta2[d] = a.sc.dtheta2[d - 1];
-    a.sc.dtheta2[0] = ((double)a.alpha * (double)a.alpha) * red[0];
+  // history shift: all entries are read before any is written (one memory latency, not D)
+  const double newest = ((double)a.alpha * (double)a.alpha) * red[0];
+  for (int base = a.D - 1; base >= 0; base -= kThreads) {        // highest chunk first
+    const int d = base - (int)threadIdx.x;                       // this thread's destination
+    double v = 0.0;
+    if (d >= 1) v = a.sc.dtheta2[d - 1];
+    __syncthreads();
+    if (d >= 1) a.sc.dtheta2[d] = v;
+    else if (d == 0) a.sc.dtheta2[0] = newest;
+    __syncthreads();
   }
 }
 
@@ -727,6 +751,7 @@ static int64_t server_blocks(int64_t p, int32_t* J_out) {
   int64_t T = (nfull + kThreads - 1) / kThreads;
   if (T < 1) T = 1;
   int64_t J = (T + 2047) / 2048;
+  if (T <= kServerJ) J = T;          // small problems: one block, no hand-over between blocks
   if (J > kServerJ) J = kServerJ;
   if (J < 1) J = 1;
   if (J_out) *J_out = (int32_t)J;
@@ -748,6 +773,7 @@ static Sweep make_sweep(int64_t p, int32_t M) {
   if (sw.T < 1) sw.T = 1;
   const int64_t max_gx = partial_slots(M);
   sw.U = (int32_t)((sw.T + max_gx - 1) / max_gx);
+  if (sw.T <= 4) sw.U = (int32_t)sw.T;   // small problems: one block per worker finishes its own skip test
   sw.Gx = (int32_t)((sw.T + sw.U - 1) / sw.U);
   return sw;
 }

@@ -230,18 +230,20 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   };
   // logits of the tile in Xs: partial products of this wave's chunks -> Zp[wave]
   auto logits = [&](const float* Xs, float* Zp) {
-    floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+    // two accumulators: a dependent chain of these matrix instructions issues at about half rate
+    floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1b = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
       const int t = wave + NW * n;
       if (t < nchunk) {
         const float4 a = *reinterpret_cast<const float4*>(&Xs[l16 * ldsF + 16 * t + 4 * lq]);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, thf[n].x, acc1, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, acc1, 0, 0, 0);
+        acc1b = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, acc1b, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, thf[n].z, acc1, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, acc1, 0, 0, 0);
+        acc1b = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, acc1b, 0, 0, 0);
       }
     }
+    acc1 = acc1 + acc1b;
 #pragma unroll
     for (int r = 0; r < 4; ++r) Zp[wave * 256 + (4 * lq + r) * 16 + l16] = acc1[r];
   };

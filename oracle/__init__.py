@@ -266,3 +266,25 @@ def grads_minibatch(kind, theta, X, y, dims, lam, idx):
                                      float(lam), _p(idx, C.c_int32), idx.shape[1],
                                      _p(G, C.c_float))
     return G
+
+
+def grad_worker(kind, theta, Xm, ym, dims, lam, N_total):
+    """One worker's gradient share: Xm[N_m][ldx], ym[N_m]; N_total = samples of all workers."""
+    Xm = _f32(Xm)
+    ym = np.ascontiguousarray(ym, np.int32)
+    theta = _f32(theta)
+    N_m, ldx = Xm.shape
+    d = np.ascontiguousarray(dims, np.int32)
+    g = np.zeros(model_params(kind, dims), np.float32)
+    L = lib()
+    pf, pi = C.c_float, C.c_int32
+    if kind == 1:
+        L.laq_oracle_grad_binlog(_p(theta, pf), _p(Xm, pf), _p(ym, pi), N_m, int(dims[0]), ldx,
+                                 int(N_total), float(lam), _p(g, pf), None)
+    elif kind == 2:
+        L.laq_oracle_grad_softmax(_p(theta, pf), _p(Xm, pf), _p(ym, pi), N_m, int(dims[0]), ldx,
+                                  int(dims[1]), int(N_total), float(lam), _p(g, pf), None)
+    else:
+        L.laq_oracle_grad_mlp(_p(theta, pf), _p(Xm, pf), _p(ym, pi), N_m, ldx, _p(d, pi), d.size,
+                              int(N_total), float(lam), _p(g, pf), None)
+    return g

@@ -21,7 +21,7 @@ namespace laq {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 
-enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2 };
+enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2, EPI_PARTIAL = 3 };
 
 struct GemmArgs {
   const float* A;      // TA ? [K][M] : [M][K]
@@ -39,6 +39,9 @@ struct GemmArgs {
   const float* Hq;
   uint32_t* rprod;
   int32_t rstride, rbase;
+  // split K (EPI_PARTIAL): blockIdx.z = batch * nsplit + split; split s multiplies rows
+  // [s ksplit, min(K, (s+1) ksplit)) of the contraction and stores its product at C + z sC
+  int32_t nsplit, ksplit;
 };
 
 // Tile loaders.  A block tile is BT = 64 NL wide and BK deep; each lane moves
@@ -185,8 +188,18 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) float gemm_smem[];
   float (*As)[BK][kLd] = reinterpret_cast<float (*)[BK][kLd]>(gemm_smem);
   float (*Bs)[BK][kLd] = reinterpret_cast<float (*)[BK][kLd]>(gemm_smem + NBUF * BK * kLd);
-  const float* A = g.A + (int64_t)blockIdx.z * g.sA;
-  const float* B = g.B + (int64_t)blockIdx.z * g.sB;
+  const float* A = g.A;
+  const float* B = g.B;
+  if (EPI == EPI_PARTIAL) {
+    const int zb = blockIdx.z / g.nsplit, zs = blockIdx.z - zb * g.nsplit;
+    const int64_t ks = (int64_t)zs * g.ksplit;
+    A += (int64_t)zb * g.sA + (TA ? ks * g.lda : ks);
+    B += (int64_t)zb * g.sB + (TB ? ks : ks * g.ldb);
+    g.K = (int32_t)((int64_t)g.K - ks < g.ksplit ? (int64_t)g.K - ks : g.ksplit);
+  } else {
+    A += (int64_t)blockIdx.z * g.sA;
+    B += (int64_t)blockIdx.z * g.sB;
+  }
   float* C = g.C + (int64_t)blockIdx.z * g.sC;
   const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -279,6 +292,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
           v = fmaxf(v + bias, 0.0f);
         } else if (EPI == EPI_MASK) {
           v = g.aux[(int64_t)row * g.ldaux + col] > 0.0f ? v : 0.0f;
+        } else if (EPI == EPI_PARTIAL) {
+          // plain product of this K range; scale, regulariser and radius follow in the slab sum
         } else {
           v = fmaf(v, g.scale, g.reg * g.aux[(int64_t)row * g.ldaux + col]);
           const uint32_t db = __float_as_uint(v - Hq[(int64_t)row * g.ldc + col]) & 0x7fffffffu;
@@ -389,18 +404,44 @@ __global__ __launch_bounds__(kThreads) void class_backward_kernel(const float* _
                                                                   const float* __restrict__ Aact, int64_t lda,
                                                                   int64_t S, int32_t K, int32_t C,
                                                                   float* __restrict__ dZprev, int64_t ldo) {
-  // block: 256 consecutive hidden units i, loops over rows
+  // block: 256 consecutive hidden units i and a run of 64 consecutive rows; the residual rows
+  // are staged in LDS (broadcast reads), four rows of activations in flight per step
   const int i = blockIdx.x * kThreads + threadIdx.x;
   float w[kCMax];
 #pragma unroll
   for (int c = 0; c < kCMax; ++c) w[c] = (i < K && c < C) ? W[(int64_t)i * C + c] : 0.0f;
-  for (int64_t n = blockIdx.y; n < S; n += gridDim.y) {
-    const float* dz = dZ + n * C;
-    float s = 0.0f;
+  constexpr int kChunk = 64;
+  __shared__ __attribute__((aligned(16))) float dzs[kChunk][kCMax];
+  for (int64_t c0 = (int64_t)blockIdx.y * kChunk; c0 < S; c0 += (int64_t)gridDim.y * kChunk) {
+    const int rows = (int)(S - c0 < kChunk ? S - c0 : kChunk);
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kChunk * kCMax; idx += kThreads) {
+      const int rr = idx / kCMax, c = idx - rr * kCMax;
+      dzs[rr][c] = (rr < rows && c < C) ? dZ[(c0 + rr) * C + c] : 0.0f;
+    }
+    __syncthreads();
+    if (i >= K) continue;
+    int rr = 0;
+    for (; rr + 4 <= rows; rr += 4) {
+      float av[4];
 #pragma unroll
-    for (int c = 0; c < kCMax; ++c)
-      if (c < C) s = fmaf(dz[c], w[c], s);
-    if (i < K) dZprev[n * ldo + i] = Aact[n * lda + i] > 0.0f ? s : 0.0f;
+      for (int u = 0; u < 4; ++u) av[u] = Aact[(c0 + rr + u) * lda + i];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < kCMax; ++c)
+          if (c < C) s = fmaf(dzs[rr + u][c], w[c], s);
+        dZprev[(c0 + rr + u) * ldo + i] = av[u] > 0.0f ? s : 0.0f;
+      }
+    }
+    for (; rr < rows; ++rr) {
+      float s = 0.0f;
+#pragma unroll
+      for (int c = 0; c < kCMax; ++c)
+        if (c < C) s = fmaf(dzs[rr][c], w[c], s);
+      dZprev[(c0 + rr) * ldo + i] = Aact[(c0 + rr) * lda + i] > 0.0f ? s : 0.0f;
+    }
   }
 }
 
@@ -419,12 +460,44 @@ __global__ __launch_bounds__(kThreads) void class_wgrad_kernel(const float* __re
   float acc[kCMax];
 #pragma unroll
   for (int c = 0; c < kCMax; ++c) acc[c] = 0.0f;
-  for (int64_t n = r0; n < r1; ++n) {
-    const float av = (i < K) ? Aact[n * lda + i] : 0.0f;
-    const float* dz = dZ + n * C;
+  // The residual rows of a chunk are staged in LDS (every lane reads the same row: broadcast
+  // reads), and four rows of activations are in flight per step: the activations are streamed
+  // once, so the loop lives on memory latency.
+  constexpr int kChunk = 64;
+  __shared__ __attribute__((aligned(16))) float dzs[kChunk][kCMax];
+  for (int64_t c0 = r0; c0 < r1; c0 += kChunk) {
+    const int rows = (int)(r1 - c0 < kChunk ? r1 - c0 : kChunk);
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kChunk * kCMax; idx += kThreads) {
+      const int rr = idx / kCMax, c = idx - rr * kCMax;
+      dzs[rr][c] = (rr < rows && c < C) ? dZ[(c0 + rr) * C + c] : 0.0f;
+    }
+    __syncthreads();
+    int rr = 0;
+    for (; rr + 4 <= rows; rr += 4) {
+      float av[4];
 #pragma unroll
-    for (int c = 0; c < kCMax; ++c)
-      if (c < C) acc[c] = fmaf(av, dz[c], acc[c]);
+      for (int u = 0; u < 4; ++u) av[u] = (i < K) ? Aact[(c0 + rr + u) * lda + i] : 0.0f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int c4 = 0; c4 < kCMax; c4 += 4) {
+          if (c4 < C) {
+            const float4 d = *reinterpret_cast<const float4*>(&dzs[rr + u][c4]);
+            acc[c4] = fmaf(av[u], d.x, acc[c4]);
+            acc[c4 + 1] = fmaf(av[u], d.y, acc[c4 + 1]);
+            acc[c4 + 2] = fmaf(av[u], d.z, acc[c4 + 2]);
+            acc[c4 + 3] = fmaf(av[u], d.w, acc[c4 + 3]);
+          }
+        }
+      }
+    }
+    for (; rr < rows; ++rr) {
+      const float av = (i < K) ? Aact[(c0 + rr) * lda + i] : 0.0f;
+#pragma unroll
+      for (int c = 0; c < kCMax; ++c)
+        if (c < C) acc[c] = fmaf(av, dzs[rr][c], acc[c]);
+    }
   }
   if (i < K) {
     float* out = part + (((int64_t)m * gridDim.y + slab) * K + i) * C;
@@ -476,9 +549,18 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float* __restric
   const int64_t rend = (int64_t)(m + 1) * N_m;
   if (r1 > rend) r1 = rend;
   if (j >= width) return;
-  float s = 0.0f;
-  for (int64_t n = r0; n < r1; ++n) s += dZ[n * ld + j];
-  part[((int64_t)m * gridDim.y + slab) * width + j] = s;
+  // eight rows in flight; partial sums combined in a fixed order
+  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+  int64_t n = r0;
+  for (; n + 8 <= r1; n += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = dZ[(n + u) * ld + j];
+    s0 += v[0]; s1 += v[1]; s2 += v[2]; s3 += v[3];
+    s0 += v[4]; s1 += v[5]; s2 += v[6]; s3 += v[7];
+  }
+  for (; n < r1; ++n) s0 += dZ[n * ld + j];
+  part[((int64_t)m * gridDim.y + slab) * width + j] = (s0 + s1) + (s2 + s3);
 }
 
 // ------------------------------------------------------------------ host side
@@ -492,6 +574,18 @@ static int gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch) {
 }
 
 
+// Weight-gradient GEMMs whose 128 x 128 tiles would leave most CUs idle (narrow layers) split the
+// sample dimension: nsplit partial products per worker, summed by slab_finish_kernel.
+static int dw_splits(const laq_ctx* ctx, int64_t in, int64_t out, int64_t N_m) {
+  const int64_t blocks128 = ((in + 127) / 128) * ((out + 127) / 128) * ctx->M;
+  if (blocks128 >= (int64_t)ctx->n_cu * 3) return 1;
+  int64_t ns = ((int64_t)ctx->n_cu * 2 + blocks128 - 1) / blocks128;
+  const int64_t max_by_k = N_m / 512;          // at least 512 samples per split
+  if (ns > max_by_k) ns = max_by_k;
+  if (ns > 16) ns = 16;
+  return ns < 2 ? 1 : (int)ns;
+}
+
 struct MlpPlan {
   int64_t S;
   int64_t act_off[LAQ_MAX_LAYERS];   // activations after hidden layer l (l = 1..L-1), floats
@@ -501,6 +595,7 @@ struct MlpPlan {
   int32_t n_slab, rows_per_slab;
   int64_t rprod_off;                 // [M][rprod_count] block maxima of |g - h|
   int32_t rprod_count;
+  int64_t splitk_off;                // [M][nsplit][in * out] partial weight gradients (largest split layer)
   int64_t total_floats;
 };
 
@@ -528,18 +623,26 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   const int64_t part_len = last_w > widest ? last_w : widest;
   pl.part_off = off; off += align_up((int64_t)ctx->M * pl.n_slab * part_len, 64);
   // one radius slot per block of every kernel that writes a segment of G
-  int64_t cnt = 0;
+  int64_t cnt = 0, splitk = 0;
   for (int l = 1; l <= n.n_layers; ++l) {
     const int64_t in = n.dims[l - 1], out = n.dims[l];
     if (l < n.n_layers) {                                                         // weight-gradient GEMM
-      const int bt = gemm_tile(ctx, in, out, ctx->M);
-      cnt += ((out + bt - 1) / bt) * ((in + bt - 1) / bt);
+      const int ns = dw_splits(ctx, in, out, N_m);
+      if (ns > 1) {
+        cnt += (in * out + kThreads - 1) / kThreads;                                // summed by slab_finish_kernel
+        const int64_t need = (int64_t)ctx->M * ns * in * out;
+        splitk = splitk > need ? splitk : need;
+      } else {
+        const int bt = gemm_tile(ctx, in, out, ctx->M);
+        cnt += ((out + bt - 1) / bt) * ((in + bt - 1) / bt);
+      }
     }
     else cnt += (in * out + kThreads - 1) / kThreads;                              // class layer
     cnt += (out + kThreads - 1) / kThreads;                                         // bias
   }
   pl.rprod_count = (int32_t)cnt;
   pl.rprod_off = off; off += align_up((int64_t)ctx->M * cnt, 64);
+  pl.splitk_off = off; off += align_up(splitk, 64);
   pl.total_floats = off;
   return pl;
 }
@@ -553,8 +656,8 @@ static size_t gemm_lds_bytes(int bt) {
 }
 
 template <bool TA, bool TB, int EPI>
-static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch) {
-  const int bt = gemm_tile(ctx, g.M, g.N, batch);
+static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool force128 = false) {
+  const int bt = force128 ? 128 : gemm_tile(ctx, g.M, g.N, batch);
   const dim3 grid((unsigned)((g.N + bt - 1) / bt), (unsigned)((g.M + bt - 1) / bt), (unsigned)batch);
   // fast loaders need aligned operand rows and no float4 straddling an operand edge
   const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4;
@@ -652,8 +755,9 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     const float* Al = ws + pl.act_off[l];
     const int width = n.dims[l];
     if (l == L - 1) {
-      int64_t rows = S < 4096 ? S : 4096;
-      const dim3 bg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)rows);
+      int64_t runs = (S + 63) / 64;                       // runs of 64 rows
+      if (runs > 8192) runs = 8192;
+      const dim3 bg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)runs);
       hipLaunchKernelGGL(class_backward_kernel, bg, dim3(kThreads), 0, ctx->stream, dZnext,
                          theta + n.offW[L - 1], Al, (int64_t)width, S, width, C, dZl, (int64_t)width);
     } else {
@@ -681,9 +785,24 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
       g.aux = theta + n.offW[l - 1]; g.ldaux = width;
       g.scale = inv_N; g.reg = reg;
       g.Hq = ctx->H + n.offW[l - 1]; g.rprod = rprod; g.rstride = rstride; g.rbase = rbase;
-      launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
-      const int bt = gemm_tile(ctx, g.M, g.N, ctx->M);
-      rbase += ((g.N + bt - 1) / bt) * ((g.M + bt - 1) / bt);
+      const int ns = dw_splits(ctx, g.M, g.N, N_m);
+      if (ns > 1) {
+        const int64_t len = (int64_t)g.M * g.N;
+        float* sp = ws + pl.splitk_off;
+        g.C = sp; g.sC = len;
+        g.nsplit = ns;
+        g.ksplit = (int32_t)align_up((N_m + ns - 1) / ns, 16);
+        launch_gemm<true, false, EPI_PARTIAL>(ctx, g, ctx->M * ns, true);
+        const unsigned wblocks = (unsigned)((len + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(slab_finish_kernel, dim3(wblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, sp,
+                           ns, len, theta + n.offW[l - 1], inv_N, reg, G + n.offW[l - 1],
+                           ctx->H + n.offW[l - 1], ctx->p_stride, rprod, rstride, rbase);
+        rbase += (int32_t)wblocks;
+      } else {
+        launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
+        const int bt = gemm_tile(ctx, g.M, g.N, ctx->M);
+        rbase += ((g.N + bt - 1) / bt) * ((g.M + bt - 1) / bt);
+      }
     }
     // db_l(m) = column sums of dZ_l(m)
     {

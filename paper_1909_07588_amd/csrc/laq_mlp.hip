@@ -156,15 +156,24 @@ struct FastLoader {
     }
     kstep = XMAJOR ? BK : (int64_t)BK * ld;
   }
-  // loads K tile number `tile`; rows of k >= K are redirected to tile 0 (in bounds) and zeroed
+  // loads K tile number `tile`; rows of k >= K are redirected to tile 0 (in bounds).  Nothing
+  // here touches the loaded values, so the wave does not wait for them before it multiplies.
   __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) const {
     const int k0 = tile * BK;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const bool kin = k0 + kk[i] < K;
       const float* src = p[i] + (kin ? (int64_t)tile * kstep : 0);
-      float4 v = *reinterpret_cast<const float4*>(src);
-      const bool ok = kin && xin[i];
+      r[i] = *reinterpret_cast<const float4*>(src);
+    }
+  }
+  // zeroes what lies outside the operand; called when the registers move to LDS
+  __device__ __forceinline__ void mask(int tile, float4 (&r)[NV]) const {
+    const int k0 = tile * BK;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const bool ok = (k0 + kk[i] < K) && xin[i];
+      float4 v = r[i];
       v.x = ok ? v.x : 0.0f; v.y = ok ? v.y : 0.0f; v.z = ok ? v.z : 0.0f; v.w = ok ? v.w : 0.0f;
       r[i] = v;
     }
@@ -177,11 +186,15 @@ struct FastLoader {
 #ifndef LAQ_GEMM_NBUF
 #define LAQ_GEMM_NBUF 2
 #endif
+// four wavefronts per SIMD: 64 accumulator registers + at most 64 others
+#ifndef LAQ_GEMM_OCC
+#define LAQ_GEMM_OCC __attribute__((amdgpu_waves_per_eu(4, 4)))
+#endif
 
 // C = op(A) op(B) with a fused epilogue.  NBUF = 2: the next K tile is written to
 // the other LDS buffer while the current one is multiplied (one barrier per tile).
 template <bool TA, bool TB, int EPI, int NL, bool FAST>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g) {
   constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
   constexpr int BT = 64 * NL, kLd = BT + 4, WT = 32 * NL;   // block tile, LDS row stride, wave tile
   constexpr int kBM = BT, kBN = BT, NV = NL * BK / 16;
@@ -231,13 +244,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
     if (TB) load_transposed<NL, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
     else load_direct<NL, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
   };
-  auto stage = [&](int buf) {
+  auto stage = [&](int buf, int k0) {
+    if (FAST) {
+      fa.mask(k0 / BK, ra);
+      fb.mask(k0 / BK, rb);
+    }
     if (TA) store_direct<NL, BK>(As[buf], ra); else store_transposed<NL, BK>(As[buf], ra);
     if (TB) store_transposed<NL, BK>(Bs[buf], rb); else store_direct<NL, BK>(Bs[buf], rb);
   };
 
   fetch(0);
-  stage(0);
+  stage(0, 0);
   __syncthreads();
   const int kh = lane >> 5, li = lane & 31;
   int cur = 0;
@@ -260,13 +277,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs g) {
     }
     if (NBUF == 2) {
       // the other buffer was last read before the previous barrier: free to overwrite
-      if (more) stage(cur ^ 1);
+      if (more) stage(cur ^ 1, k0 + BK);
       __syncthreads();
       cur ^= 1;
     } else {
       __syncthreads();
       if (more) {
-        stage(0);
+        stage(0, k0 + BK);
         __syncthreads();
       }
     }

@@ -132,11 +132,11 @@ def model_rooflines(w, ph, traffic):
         dA = sum(2 * S * d[i] * d[i + 1] for i in range(1, len(d) - 1))
         flops = 2 * fwd + dA                      # forward + weight gradients + activation gradients
         out["worker_grads"] = _roofline("mfma", flops / (ph[0] * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s",
-                                        traffic.get(w.name + ":worker_grads"), "gemm_kernel (fp32 MFMA) group")
+                                        traffic.get(w.name + ":worker_grads"), "gemm_kernel (fp32 MFMA) + class-layer, bias and finish kernels")
     else:
         gb = (x_bytes + 4 * elems + 4 * w.p) / 1e9   # read X once, read theta, write G
         out["worker_grads"] = _roofline("hbm", gb / (ph[0] * 1e-3), HBM_PEAK_GBS, "GB/s",
-                                        traffic.get(w.name + ":worker_grads"), "softmax_grad_kernel group")
+                                        traffic.get(w.name + ":worker_grads"), "softmax_grad_mfma_kernel + finish_grad_kernel")
     gq = elems * (8 + w.b / 8) / 1e9
     out["quantize_skip"] = _roofline("hbm", gq / (ph[1] * 1e-3), HBM_PEAK_GBS, "GB/s",
                                      traffic.get(w.name + ":quantize_skip"), "radius_kernel + codes_kernel")

@@ -35,6 +35,15 @@ def test_size_queries_need_no_gpu():
     assert L.laq_workspace_bytes(10, 7850, 3, 10) >= 10 * 7852 * 4 + 7852 * 4
     assert L.laq_workspace_bytes(0, 10, 3, 10) == 0
     assert L.laq_workspace_bytes(1, 10, 17, 10) == 0
+    # limits: p < 2^31, M <= 65535, 1 <= D <= 4096, b in 1..16 or the identity quantizer's 32
+    assert L.laq_workspace_bytes(1, ctypes.c_int64(1 << 31), 4, 1) == 0
+    assert L.laq_workspace_bytes(1, ctypes.c_int64((1 << 31) - 1), 4, 1) > (1 << 33)
+    assert L.laq_workspace_bytes(65536, 10, 4, 1) == 0
+    assert L.laq_workspace_bytes(65535, 10, 4, 1) > 0
+    assert L.laq_workspace_bytes(1, 10, 4, 4097) == 0
+    assert L.laq_workspace_bytes(1, 10, 0, 1) == 0
+    assert L.laq_workspace_bytes(1, 10, 32, 1) > 0 and laq.w_stride(10, 32) == 16
+    assert L.laq_workspace_bytes(1, 10, 31, 1) == 0
 
 
 def test_create_rejects_bad_arguments_before_touching_the_device():

@@ -132,186 +132,192 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
 //   Z[16 rows][C] = X[16][F] Theta^T        and        Gacc[C][F] += R^T[C][16] X[16][F].
 // They map onto v_mfma_f32_16x16x4_f32 with the class dimension padded to 16.
 // One block of 16 wavefronts owns a range of rows and walks it in tiles of 16
-// rows.  Tiles are copied once from HBM to LDS (coalesced, prefetched into
-// registers two tiles ahead, double-buffered in LDS).  For the logits the
-// waves split the feature dimension -- wave w always multiplies chunks
-// w, w+16, ..., so its fragments of Theta stay in registers for the whole
-// kernel -- and their partial products are summed through LDS.  The softmax
-// of tile n runs on 4 waves while the other 12 already form the logits of
-// tile n+1.  For the rank-16 update the waves split the feature tiles and keep
-// their part of Gacc in registers for the whole row range.  LDS allows one
-// block per CU, hence the wide block (4 waves per SIMD).
+// rows.  Wave w owns the feature chunks w, w+16, ... of 16 columns in BOTH
+// products, so its slice of every tile is private to it:
+//   * it loads the slice straight from HBM in the A-operand layout of the
+//     logits (lane = row, 4 consecutive columns), one tile ahead;
+//   * the logits' matrix instructions take these registers directly and leave
+//     the wave's partial product in LDS (Zp);
+//   * the registers are then parked in the wave's own LDS slice, from which the
+//     rank-16 update reads them back in its B-operand layout (lane = column);
+//     no other wave touches the slice, so no barrier guards it.
+// The block meets twice per tile: once after the partial logits are written and
+// once after the residuals R = softmax(Z) - onehot(y) are (wave w does row w).
+// Theta fragments and the wave's part of Gacc stay in registers for the whole
+// kernel.  LDS (about 70 KB) and registers allow one block per CU.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kRT = 16;          // rows per tile
 constexpr int kSmxWaves = 16;
 
+// value held by lane (i + N) mod 16 of the same 16-lane row (data-parallel primitive, no LDS)
+template <int N>
+__device__ __forceinline__ float row_ror(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xf, 0xf, false));
+}
+
 template <int TMAX>
 __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
-    int64_t N_m, int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, int32_t ldsF,
-    float* __restrict__ part) {
-  constexpr int NW = kSmxWaves, NT = 64 * NW;
+    int64_t N_m, int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, float* __restrict__ part) {
+  constexpr int NW = kSmxWaves;
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  float* Xs0 = smem;                         // [16][ldsF]
-  float* Xs1 = Xs0 + kRT * ldsF;
-  float* Zp0 = Xs1 + kRT * ldsF;             // [NW][16][16] partial logits, two buffers
-  float* Zp1 = Zp0 + NW * 256;
-  float* Rs = Zp1 + NW * 256;                // [16][16] residuals P - Y
-  int* Ys = reinterpret_cast<int*>(Rs + 256);  // [2][16] labels, indexed like the X buffers
-
   const int m = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
   const float* Xm = X + (int64_t)m * N_m * ldx;
   const int32_t* ym = y + (int64_t)m * N_m;
-  const int nchunk = (F + 15) / 16, FP = nchunk * 16, nf4 = FP / 4;
+  const int nchunk = (F + 15) / 16;
+  float* Xs = smem;                          // [2][nchunk][256]: chunk t belongs to wave t % 16
+  float* Zp = Xs + 2 * nchunk * 256;         // [2][NW][64] float4: partial logits in accumulator layout
+  float* Rs = Zp + 2 * NW * 256;             // [16][16] residuals P - Y
 
-  // Theta fragments of this wave's feature chunks (B operand of the logits): lane
-  // (class j = l16, quarter lq) holds Theta[j][16 t + 4 lq .. +3], zero past C or F.
-  // They go through LDS (staged in the first tile buffer) rather than straight
-  // from global memory into registers: the matrix instructions of the main loop
-  // then depend on LDS counters only and never wait behind the tile prefetch.
-  for (int idx = tid; idx < kRT * FP; idx += NT) {
-    const int c = idx / FP, f = idx - c * FP;
-    Xs0[c * ldsF + f] = (c < C && f < F) ? theta[(int64_t)c * F + f] : 0.0f;
-  }
-  __syncthreads();
+  // Theta fragments (B operand of the logits): lane (class l16, quarter lq) holds
+  // Theta[l16][16 t + 4 lq .. +3] for this wave's chunks, zero past C or F.
   float4 thf[TMAX];
 #pragma unroll
   for (int n = 0; n < TMAX; ++n) {
-    const int t = wave + NW * n;
-    thf[n] = t < nchunk ? *reinterpret_cast<const float4*>(&Xs0[l16 * ldsF + 16 * t + 4 * lq])
-                        : make_float4(0.f, 0.f, 0.f, 0.f);
+    const int f = 16 * (wave + NW * n) + 4 * lq;
+    const bool on = l16 < C;
+    const float* tp = theta + (int64_t)(on ? l16 : 0) * F;
+    float4 v;
+    v.x = (on && f < F) ? tp[f < F ? f : 0] : 0.0f;
+    v.y = (on && f + 1 < F) ? tp[f + 1 < F ? f + 1 : 0] : 0.0f;
+    v.z = (on && f + 2 < F) ? tp[f + 2 < F ? f + 2 : 0] : 0.0f;
+    v.w = (on && f + 3 < F) ? tp[f + 3 < F ? f + 3 : 0] : 0.0f;
+    thf[n] = v;
   }
-  __syncthreads();
 
   const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
   int64_t r_end = r_begin + rows_per_block;
   if (r_end > N_m) r_end = N_m;
-  const int64_t last_row = r_end - 1;
 
-  // Tile prefetch: PF unconditional 16-byte loads per lane (row and column
-  // clamped into the matrix; rows are padded to ldx, a multiple of 4, so a
-  // float4 that starts below F stays inside its row); rows >= r_end and columns
-  // >= F are zeroed when the registers are written to LDS.
-  constexpr int PF = (kRT * NW * TMAX * 16 / 4 + NT - 1) / NT;
-  float4 pre[PF];
+  // LDS word of element (row, col) of a 16 x 16 chunk: 16-byte slot 4 rho(row) + (col/4 ^ sigma(row)),
+  // rho(row) = row ^ bit 2 of row, sigma(row) = (row / 2) % 4: 16-byte accesses by (row, quarter)
+  // lanes and 4-byte accesses by (column, row group) lanes both spread over the banks.
+  const int wr_off = ((4 * (l16 ^ ((l16 >> 2) & 1))) + (lq ^ ((l16 >> 1) & 3))) * 4;
+  int rd_off[4];                             // matrix instruction u of the update contracts rows 4 u + lq
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int row = 4 * u + lq;
+    rd_off[u] = ((4 * (row ^ ((row >> 2) & 1))) + ((l16 >> 2) ^ ((row >> 1) & 3))) * 4 + (l16 & 3);
+  }
+
+  // This wave's slice of a tile, HBM -> registers: lane (row l16, quarter lq) takes 16 bytes per
+  // chunk.  Rows past r_end are clamped to the last row (their residuals are zero), columns are
+  // clamped into the row (rows are padded to ldx, a multiple of 4) and zeroed when consumed.
+  const int nf4r = (F + 3) >> 2;
+  float4 pre[TMAX];
   int ypre = 0;
-  auto gload = [&](int64_t r0) {
-    if (tid < kRT) ypre = ym[(r0 + tid < r_end) ? r0 + tid : last_row];
-#pragma unroll
-    for (int q = 0; q < PF; ++q) {
-      int idx = tid + NT * q;
-      idx = idx < kRT * nf4 ? idx : kRT * nf4 - 1;
-      const int row = idx / nf4;
-      int f = (idx - row * nf4) * 4;
-      f = f < F ? f : 0;
-      int64_t gr = r0 + row;
-      gr = gr < r_end ? gr : last_row;
-      pre[q] = *reinterpret_cast<const float4*>(Xm + gr * ldx + f);
-    }
-  };
-  auto lstore = [&](float* buf, int which, int64_t r0) {
-    if (tid < kRT) Ys[which * kRT + tid] = ypre;
-#pragma unroll
-    for (int q = 0; q < PF; ++q) {
-      const int idx = tid + NT * q;
-      if (idx < kRT * nf4) {
-        const int row = idx / nf4, f = (idx - row * nf4) * 4;
-        const bool rv = r0 + row < r_end;
-        float4 v = pre[q];
-        v.x = (rv && f < F) ? v.x : 0.0f;
-        v.y = (rv && f + 1 < F) ? v.y : 0.0f;
-        v.z = (rv && f + 2 < F) ? v.z : 0.0f;
-        v.w = (rv && f + 3 < F) ? v.w : 0.0f;
-        *reinterpret_cast<float4*>(&buf[row * ldsF + f]) = v;
-      }
-    }
-  };
-  // logits of the tile in Xs: partial products of this wave's chunks -> Zp[wave]
-  auto logits = [&](const float* Xs, float* Zp) {
-    // two accumulators: a dependent chain of these matrix instructions issues at about half rate
-    floatx4 acc1 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1b = floatx4{0.f, 0.f, 0.f, 0.f};
+  auto gload = [&](int64_t r0, float4 (&pre)[TMAX], int& ylab) {
+    // uniform tile base + 32-bit lane offsets (few address registers)
+    int64_t rb = r0 < r_end ? r0 : r_end - 1;                 // first row of the tile, clamped
+    const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
+    const float* base = Xm + rb * ldx;
+    const uint32_t row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
-      const int t = wave + NW * n;
-      if (t < nchunk) {
-        const float4 a = *reinterpret_cast<const float4*>(&Xs[l16 * ldsF + 16 * t + 4 * lq]);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, thf[n].x, acc1, 0, 0, 0);
-        acc1b = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, acc1b, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, thf[n].z, acc1, 0, 0, 0);
-        acc1b = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, acc1b, 0, 0, 0);
-      }
+      uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;   // float4 column
+      q = q < (uint32_t)nf4r ? q : 0u;
+      pre[n] = *reinterpret_cast<const float4*>(base + (row_off + 4u * q));
     }
-    acc1 = acc1 + acc1b;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) Zp[wave * 256 + (4 * lq + r) * 16 + l16] = acc1[r];
+    ylab = ym[rb + (wave < rows_valid ? wave : rows_valid - 1)];     // this wave's softmax row
   };
 
   floatx4 acc2[TMAX];
 #pragma unroll
   for (int n = 0; n < TMAX; ++n) acc2[n] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // prologue: tile 0 in Xs0 with its logits in Zp0, tile 1 in Xs1
-  gload(r_begin);
-  lstore(Xs0, 0, r_begin);
-  const bool have1 = r_begin + kRT < r_end;
-  if (have1) gload(r_begin + kRT);
-  __syncthreads();
-  logits(Xs0, Zp0);
-  if (have1) lstore(Xs1, 1, r_begin + kRT);
-  __syncthreads();
-
-  int cur = 0;
-  for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
-    float* Xc = cur ? Xs1 : Xs0;
-    float* Xn = cur ? Xs0 : Xs1;
-    float* Zc = cur ? Zp1 : Zp0;
-    float* Zn = cur ? Zp0 : Zp1;
-    const bool more1 = r0 + kRT < r_end;          // tile n+1 exists (already in Xn)
-    const bool more2 = r0 + 2 * kRT < r_end;      // tile n+2 exists
-    if (more2) gload(r0 + 2 * kRT);
-
-    // softmax of tile n on waves 0..3 (lane = row i, class j), logits of tile n+1 on all
-    if (tid < 256) {
-      const int i = tid >> 4, j = tid & 15;
-      float z = Zc[tid];
+  // logits of the tile in pre -> Zp[buf][wave]; the tile -> this wave's LDS slice of buffer buf
+  auto consume = [&](const float4 (&pre)[TMAX], int buf) {
+    floatx4 za = floatx4{0.f, 0.f, 0.f, 0.f}, zb = floatx4{0.f, 0.f, 0.f, 0.f};
+    float* Xb = Xs + buf * nchunk * 256;
 #pragma unroll
-      for (int wv = 1; wv < NW; ++wv) z += Zc[wv * 256 + tid];
-      const bool valid = j < C;
-      float zm = valid ? z : -INFINITY;
-#pragma unroll
-      for (int off = 8; off > 0; off >>= 1) zm = fmaxf(zm, __shfl_xor(zm, off));
-      const float e = valid ? expf(z - zm) : 0.0f;
-      float den = e;
-#pragma unroll
-      for (int off = 8; off > 0; off >>= 1) den += __shfl_xor(den, off);
-      float rv = 0.0f;
-      if (valid && r0 + i < r_end) rv = e / den - (j == Ys[cur * kRT + i] ? 1.0f : 0.0f);
-      Rs[tid] = rv;
+    for (int n = 0; n < TMAX; ++n) {
+      const int t = wave + NW * n;
+      if (t < nchunk) {                                       // uniform over the wave
+        float4 a = pre[n];
+        const int f = 16 * t + 4 * lq;
+        a.x = f < F ? a.x : 0.0f;
+        a.y = f + 1 < F ? a.y : 0.0f;
+        a.z = f + 2 < F ? a.z : 0.0f;
+        a.w = f + 3 < F ? a.w : 0.0f;
+        za = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, thf[n].x, za, 0, 0, 0);
+        zb = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, zb, 0, 0, 0);
+        za = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, thf[n].z, za, 0, 0, 0);
+        zb = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, zb, 0, 0, 0);
+        *reinterpret_cast<float4*>(&Xb[t * 256 + wr_off]) = a;
+      }
     }
-    if (more1) logits(Xn, Zn);
-    __syncthreads();
+    za = za + zb;
+    *reinterpret_cast<floatx4*>(&Zp[((buf * NW + wave) * 64 + lane) * 4]) = za;   // element r: row 4 lq + r, class l16
+  };
 
-    // rank-16 update with tile n: wave w owns feature tiles ft = w, w+NW, ...
+  // residuals of row `wave` of the tile whose partial logits are in Zp[buf]
+  auto softmax_row = [&](int buf, int64_t r0, int ylab) {
+    const int i = wave;
+    const int widx = ((i >> 2) * 16 + l16) * 4 + (i & 3);   // lane (l16, i / 4), element i % 4
+    const float* Zb = Zp + buf * NW * 256;
+    float z = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) z += Zb[(4 * lq + k) * 256 + widx];   // partials of waves 4 lq .. 4 lq + 3
+    z += __shfl_xor(z, 16);
+    z += __shfl_xor(z, 32);
+    const bool valid = l16 < C;
+    float zm = valid ? z : -INFINITY;
+    zm = fmaxf(zm, row_ror<8>(zm));
+    zm = fmaxf(zm, row_ror<4>(zm));
+    zm = fmaxf(zm, row_ror<2>(zm));
+    zm = fmaxf(zm, row_ror<1>(zm));
+    const float e = valid ? expf(z - zm) : 0.0f;
+    float den = e;
+    den += row_ror<8>(den);
+    den += row_ror<4>(den);
+    den += row_ror<2>(den);
+    den += row_ror<1>(den);
+    float rv = 0.0f;
+    if (valid && r0 + i < r_end) rv = e / den - (l16 == ylab ? 1.0f : 0.0f);
+    if (lq == 0) Rs[i * 16 + l16] = rv;
+  };
+  // rank-16 update with the tile parked in buffer buf
+  auto rank_update = [&](int buf) {
+    const float* Xb = Xs + buf * nchunk * 256;
     float ar[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) ar[u] = Rs[(4 * u + lq) * 16 + l16];
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
-      const int ft = wave + NW * n;
-      if (ft < nchunk) {
+      const int t = wave + NW * n;
+      if (t < nchunk) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float b = Xc[(4 * u + lq) * ldsF + 16 * ft + l16];
+          const float b = Xb[t * 256 + rd_off[u]];
           acc2[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[u], b, acc2[n], 0, 0, 0);
         }
       }
     }
-    __syncthreads();                               // tile n fully consumed: its buffer is free
-    if (more2) lstore(Xc, cur, r0 + 2 * kRT);
-    __syncthreads();
-    cur ^= 1;
+  };
+
+  // Pipeline (tile n): [barrier] logits of tile n+1 from the registers, which are refilled at once
+  // with tile n+2 (in flight during the softmax and the rank update); softmax of tile n; [barrier]
+  // rank update with tile n.  Everything is unconditional: past the block's range the loads are
+  // clamped to its last row and the results are never used (under branches the compiler merges
+  // register sets with copies and waits for loads right after issuing them).
+  if (r_begin >= r_end) return;                     // (uniform; cannot happen with the host's grid)
+  gload(r_begin, pre, ypre);
+  consume(pre, 0);
+  int ycur = ypre;                                  // label of this wave's row in the tile of Zp[0]
+  gload(r_begin + kRT, pre, ypre);
+  int buf = 0;
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
+    __syncthreads();                                // Zp[buf] complete; Rs and the other buffers free
+    consume(pre, buf ^ 1);
+    const int ynext = ypre;
+    gload(r0 + 2 * kRT, pre, ypre);
+    softmax_row(buf, r0, ycur);
+    __syncthreads();                                // Rs complete
+    rank_update(buf);
+    ycur = ynext;
+    buf ^= 1;
   }
 
   float* out = part + ((int64_t)m * gridDim.x + blockIdx.x) * ((int64_t)C * F);
@@ -420,20 +426,18 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
 
 // ------------------------------------------------------------------ host side
 
-// LDS layout of the matrix-core softmax kernel: row stride (floats) and bytes; 0 if it does not fit.
-static size_t softmax_mfma_lds(const laq_ctx* ctx, int* ldsF_out) {
+// LDS bytes of the matrix-core softmax kernel (tile slices, partial logits, residuals); 0 if the
+// model does not fit it.
+static size_t softmax_mfma_lds(const laq_ctx* ctx) {
   if (ctx->kind != LAQ_MODEL_SOFTMAX || ctx->C > 16) return 0;
-  const int FP = (ctx->F + 15) / 16 * 16;
-  if (FP > 16 * kSmxWaves * 4) return 0;
-  const int pad = (20 - FP % 32 + 32) % 32;       // row stride = 20 (mod 32) banks: conflict-free b128 reads
-  const int ldsF = FP + pad;
-  if (ldsF_out) *ldsF_out = ldsF;
-  const size_t bytes = ((size_t)2 * kRT * ldsF + (2 * kSmxWaves + 1) * 256 + 2 * kRT) * sizeof(float);
+  const int nchunk = (ctx->F + 15) / 16;
+  if (nchunk > kSmxWaves * 4) return 0;
+  const size_t bytes = ((size_t)2 * nchunk * 256 + (2 * kSmxWaves + 1) * 256) * sizeof(float);
   return bytes <= 160 * 1024 ? bytes : 0;
 }
 
 static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block) {
-  if (softmax_mfma_lds(ctx, nullptr)) {
+  if (softmax_mfma_lds(ctx)) {
     // one block per CU at most (LDS-bound occupancy), whole row tiles per block
     const int RT = kRT;
     int64_t want = ctx->n_cu / ctx->M;
@@ -495,8 +499,7 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   float* part = reinterpret_cast<float*>(ctx->model_ws);
   const dim3 grid((unsigned)nb, (unsigned)ctx->M);
   const int kf = (ctx->F + 63) / 64;
-  int ldsF = 0;
-  const size_t mfma_lds = softmax_mfma_lds(ctx, &ldsF);
+  const size_t mfma_lds = softmax_mfma_lds(ctx);
   if (mfma_lds) {
     const int nchunk = (ctx->F + 15) / 16;
 #define LAQ_SMM(T)                                                                                     \
@@ -505,7 +508,7 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                               \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
     hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta, ctx->X, ctx->y,   \
-                       ctx->N_m, ctx->ldx, ctx->F, ctx->C, rpb, ldsF, part);                            \
+                       ctx->N_m, ctx->ldx, ctx->F, ctx->C, rpb, part);                                  \
   } while (0)
     if (nchunk <= kSmxWaves) LAQ_SMM(1);
     else if (nchunk <= 2 * kSmxWaves) LAQ_SMM(2);

@@ -310,10 +310,20 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   int buf = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
     __syncthreads();                                // Zp[buf] complete; Rs and the other buffers free
-    consume(pre, buf ^ 1);
-    const int ynext = ypre;
-    gload(r0 + 2 * kRT, pre, ypre);
-    softmax_row(buf, r0, ycur);
+    // Of the four waves on a SIMD, two multiply first and two do their softmax row first, so the
+    // matrix pipe has work while the other pair runs vector code.
+    int ynext;
+    if (wave & 8) {
+      softmax_row(buf, r0, ycur);
+      consume(pre, buf ^ 1);
+      ynext = ypre;
+      gload(r0 + 2 * kRT, pre, ypre);
+    } else {
+      consume(pre, buf ^ 1);
+      ynext = ypre;
+      gload(r0 + 2 * kRT, pre, ypre);
+      softmax_row(buf, r0, ycur);
+    }
     __syncthreads();                                // Rs complete
     rank_update(buf);
     ycur = ynext;

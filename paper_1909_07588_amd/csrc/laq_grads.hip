@@ -142,9 +142,14 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
 //     rank-16 update reads them back in its B-operand layout (lane = column);
 //     no other wave touches the slice, so no barrier guards it.
 // The block meets twice per tile: once after the partial logits are written and
-// once after the residuals R = softmax(Z) - onehot(y) are (wave w does row w).
+// once after the residuals R = softmax(Z) - onehot(y) are.  The softmax runs on
+// four waves, one per SIMD, each lane holding one of the 256 entries: measured
+// here, vector instructions and matrix instructions of the waves on a SIMD do
+// not overlap much, so the softmax is kept to as few wave instructions as
+// possible, given priority, and the other twelve waves multiply meanwhile.
 // Theta fragments and the wave's part of Gacc stay in registers for the whole
-// kernel.  LDS (about 70 KB) and registers allow one block per CU.
+// kernel.  LDS (two slice buffers, two partial-logit buffers: about 135 KB) and
+// registers allow one block per CU.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kRT = 16;          // rows per tile
 constexpr int kSmxWaves = 16;
@@ -169,7 +174,7 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   const int nchunk = (F + 15) / 16;
   float* Xs = smem;                          // [2][nchunk][256]: chunk t belongs to wave t % 16
   float* Zp = Xs + 2 * nchunk * 256;         // [2][NW][64] float4: partial logits in accumulator layout
-  float* Rs = Zp + 2 * NW * 256;             // [16][16] residuals P - Y
+  float* Rs = Zp + 2 * NW * 256;             // [2][16][16] residuals P - Y
 
   // Theta fragments (B operand of the logits): lane (class l16, quarter lq) holds
   // Theta[l16][16 t + 4 lq .. +3] for this wave's chunks, zero past C or F.
@@ -220,7 +225,8 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
       q = q < (uint32_t)nf4r ? q : 0u;
       pre[n] = *reinterpret_cast<const float4*>(base + (row_off + 4u * q));
     }
-    ylab = ym[rb + (wave < rows_valid ? wave : rows_valid - 1)];     // this wave's softmax row
+    const int yrow = 4 * (wave & 3) + lq;                           // softmax waves 0..3: rows 4 wave + lq
+    ylab = ym[rb + (yrow < rows_valid ? yrow : rows_valid - 1)];
   };
 
   floatx4 acc2[TMAX];
@@ -252,16 +258,15 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     *reinterpret_cast<floatx4*>(&Zp[((buf * NW + wave) * 64 + lane) * 4]) = za;   // element r: row 4 lq + r, class l16
   };
 
-  // residuals of row `wave` of the tile whose partial logits are in Zp[buf]
-  auto softmax_row = [&](int buf, int64_t r0, int ylab) {
-    const int i = wave;
-    const int widx = ((i >> 2) * 16 + l16) * 4 + (i & 3);   // lane (l16, i / 4), element i % 4
-    const float* Zb = Zp + buf * NW * 256;
-    float z = 0.0f;
+  // Residuals of rows 4 wave .. 4 wave + 3 (waves 0..3, one per SIMD: every lane holds one of the
+  // 256 entries; the vector ALU and the matrix pipe of a SIMD share one issue port, so the softmax
+  // must cost as few wave instructions as possible).  Lane (class l16, lq) handles row 4 wave + lq.
+  auto softmax_rows = [&](int buf, int64_t r0, int ylab) {
+    const int i = 4 * wave + lq;
+    const float* Zb = Zp + buf * NW * 256 + (wave * 16 + l16) * 4 + lq;   // element lq of lane (l16, wave)
+    float z = Zb[0];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) z += Zb[(4 * lq + k) * 256 + widx];   // partials of waves 4 lq .. 4 lq + 3
-    z += __shfl_xor(z, 16);
-    z += __shfl_xor(z, 32);
+    for (int wv = 1; wv < NW; ++wv) z += Zb[wv * 256];
     const bool valid = l16 < C;
     float zm = valid ? z : -INFINITY;
     zm = fmaxf(zm, row_ror<8>(zm));
@@ -276,14 +281,14 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     den += row_ror<1>(den);
     float rv = 0.0f;
     if (valid && r0 + i < r_end) rv = e / den - (l16 == ylab ? 1.0f : 0.0f);
-    if (lq == 0) Rs[i * 16 + l16] = rv;
+    Rs[buf * 256 + i * 16 + l16] = rv;
   };
   // rank-16 update with the tile parked in buffer buf
   auto rank_update = [&](int buf) {
     const float* Xb = Xs + buf * nchunk * 256;
     float ar[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) ar[u] = Rs[(4 * u + lq) * 16 + l16];
+    for (int u = 0; u < 4; ++u) ar[u] = Rs[buf * 256 + (4 * u + lq) * 16 + l16];
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
       const int t = wave + NW * n;
@@ -297,34 +302,30 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     }
   };
 
-  // Pipeline (tile n): [barrier] logits of tile n+1 from the registers, which are refilled at once
-  // with tile n+2 (in flight during the softmax and the rank update); softmax of tile n; [barrier]
-  // rank update with tile n.  Everything is unconditional: past the block's range the loads are
-  // clamped to its last row and the results are never used (under branches the compiler merges
-  // register sets with copies and waits for loads right after issuing them).
+  // Pipeline for tile n: [barrier: partial logits of tile n complete] waves 0..3 (one per SIMD)
+  // turn them into residuals; every wave forms the logits of tile n+1 from its registers, which
+  // then take tile n+2 (in flight for the rest of the step); [barrier: residuals complete] rank
+  // update with tile n.  The logits step parks tile n+1 in the slice buffer the update is not
+  // using.  Everything is unconditional: past the block's range the loads are clamped to its last
+  // row and the results are never used (under branches the compiler merges register sets with
+  // copies and waits for loads right after issuing them: a memory latency per tile).
   if (r_begin >= r_end) return;                     // (uniform; cannot happen with the host's grid)
   gload(r_begin, pre, ypre);
   consume(pre, 0);
-  int ycur = ypre;                                  // label of this wave's row in the tile of Zp[0]
+  int ycur = ypre;                                  // labels of this lane's softmax row in the tile of Zp[0]
   gload(r_begin + kRT, pre, ypre);
   int buf = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
-    __syncthreads();                                // Zp[buf] complete; Rs and the other buffers free
-    // Of the four waves on a SIMD, two multiply first and two do their softmax row first, so the
-    // matrix pipe has work while the other pair runs vector code.
-    int ynext;
-    if (wave & 8) {
-      softmax_row(buf, r0, ycur);
-      consume(pre, buf ^ 1);
-      ynext = ypre;
-      gload(r0 + 2 * kRT, pre, ypre);
-    } else {
-      consume(pre, buf ^ 1);
-      ynext = ypre;
-      gload(r0 + 2 * kRT, pre, ypre);
-      softmax_row(buf, r0, ycur);
+    __syncthreads();                                // Zp[buf] complete; Zp[buf ^ 1] and slice buffer buf ^ 1 free
+    if (wave < 4) {                                 // uniform over the wave
+      __builtin_amdgcn_s_setprio(2);                // the wave with the extra work goes first
+      softmax_rows(buf, r0, ycur);
+      __builtin_amdgcn_s_setprio(0);
     }
-    __syncthreads();                                // Rs complete
+    consume(pre, buf ^ 1);
+    const int ynext = ypre;
+    gload(r0 + 2 * kRT, pre, ypre);
+    __syncthreads();                                // Rs[buf] complete
     rank_update(buf);
     ycur = ynext;
     buf ^= 1;
@@ -442,7 +443,7 @@ static size_t softmax_mfma_lds(const laq_ctx* ctx) {
   if (ctx->kind != LAQ_MODEL_SOFTMAX || ctx->C > 16) return 0;
   const int nchunk = (ctx->F + 15) / 16;
   if (nchunk > kSmxWaves * 4) return 0;
-  const size_t bytes = ((size_t)2 * nchunk * 256 + (2 * kSmxWaves + 1) * 256) * sizeof(float);
+  const size_t bytes = ((size_t)2 * nchunk * 256 + (2 * kSmxWaves + 2) * 256) * sizeof(float);
   return bytes <= 160 * 1024 ? bytes : 0;
 }
 

@@ -129,15 +129,17 @@ __device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], con
 template <int NL, int BK, bool XMAJOR>
 struct FastLoader {
   static constexpr int NV = NL * BK / 16;
-  const float* p[NV];   // source address of this lane's float4 in K tile 0 (clamped into the operand)
+  const float* q[NV];   // source address of this lane's float4 in the next K tile to load (clamped into the operand)
   int kk[NV];           // its k offset inside the tile
   bool xin[NV];         // its row/column lies inside the operand
   int64_t kstep;        // address advance per K tile
   int K;
+  bool all_in;          // the whole block tile lies inside the operand (uniform over the block)
 
   __device__ __forceinline__ void init(const float* S, int64_t ld, int K_, int X, int x0) {
     const int t = threadIdx.x;
     K = K_;
+    all_in = x0 + 64 * NL <= X;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       int kq, xx;
@@ -152,24 +154,33 @@ struct FastLoader {
       const int x = x0 + xx;
       xin[i] = x < X;
       const int xc = xin[i] ? x : 0;
-      p[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
+      q[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
     }
     kstep = XMAJOR ? BK : (int64_t)BK * ld;
   }
-  // loads K tile number `tile`; rows of k >= K are redirected to tile 0 (in bounds).  Nothing
-  // here touches the loaded values, so the wave does not wait for them before it multiplies.
-  __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) const {
+  // Loads K tile number `tile` (tiles are requested in order 0, 1, 2, ...) and advances the
+  // pointers.  In the last, partial tile, rows of k >= K are redirected to tile 0 (in bounds).
+  // Nothing here touches the loaded values, so the wave does not wait for them before it multiplies.
+  __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) {
     const int k0 = tile * BK;
+    if (k0 + BK <= K) {                                   // uniform
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const bool kin = k0 + kk[i] < K;
-      const float* src = p[i] + (kin ? (int64_t)tile * kstep : 0);
-      r[i] = *reinterpret_cast<const float4*>(src);
+      for (int i = 0; i < NV; ++i) {
+        r[i] = *reinterpret_cast<const float4*>(q[i]);
+        q[i] += kstep;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const bool kin = k0 + kk[i] < K;
+        r[i] = *reinterpret_cast<const float4*>(kin ? q[i] : q[i] - (int64_t)tile * kstep);
+      }
     }
   }
   // zeroes what lies outside the operand; called when the registers move to LDS
   __device__ __forceinline__ void mask(int tile, float4 (&r)[NV]) const {
     const int k0 = tile * BK;
+    if (all_in && k0 + BK <= K) return;                   // uniform: interior tile, nothing to zero
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const bool ok = (k0 + kk[i] < K) && xin[i];

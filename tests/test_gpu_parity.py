@@ -65,6 +65,25 @@ def test_many_tiles_and_ragged_tail(b, p):
         Gd[:, :p].copy_(torch.from_numpy(G))
 
 
+@pytest.mark.parametrize("M,p,b,D", [(300, 100, 4, 4), (1500, 37, 2, 3), (70, 5000, 8, 300), (257, 4100, 3, 257)])
+def test_many_workers_and_long_history(M, p, b, D):
+    """More workers than one block's threads (the server's list of uploaders is built in several
+    rounds), more workers than 64 (fewer partial slots each), a history longer than the part of it
+    that is staged in LDS."""
+    rng = np.random.default_rng(M + p)
+    ctx, st, theta = make_pair(M, p, b, D=D, xi=0.5 / D, t_bar=D + 2, alpha=0.05)
+    for it in range(3):
+        _random_state(st, rng, scale=0.5)
+        st.dtheta2[:] = rng.random(D) * 1e-3
+        theta.copy_(torch.from_numpy(st.theta))
+        push_state(ctx, st)
+        scale = (10.0 ** rng.uniform(-3, 0, (M, 1))).astype(np.float32)
+        G = (st.H + scale * rng.standard_normal((M, p))).astype(np.float32)
+        Gd = to_dev_G(ctx, G)
+        msgs, _ = check_quantize(ctx, st, Gd, G)
+        check_server(ctx, st, theta, msgs, G)
+
+
 def test_teacher_forced_run_skips_and_uploads():
     """30 iterations of drifting synthetic gradients: every mask, code and iterate equal."""
     M, p, b = 12, 40_000, 4

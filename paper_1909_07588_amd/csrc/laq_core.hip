@@ -201,7 +201,8 @@ __device__ __forceinline__ void stage_history(const QuantArgs& a, double* hterm)
 // The skip rule (eqs. 7a-7b) for worker m in binary64 with a fixed operation order, and the
 // per-call stash read by the server step; run by one thread.
 __device__ __forceinline__ void apply_skip_rule(const QuantArgs& a, int m, float R, bool finite, double lhs,
-                                                double E2, long long Sq, const double* hterm) {
+                                                double E2, long long Sq, const double* hterm, double ehat2,
+                                                int t_m) {
   // hterm[d] = xi_d * ||theta^{k+1-d} - theta^{k-d}||^2, fetched by D threads at once (a loop of
   // dependent global loads on one thread would cost a memory latency per term)
   double Hsum = 0.0;
@@ -212,11 +213,11 @@ __device__ __forceinline__ void apply_skip_rule(const QuantArgs& a, int m, float
   const double a2 = (double)a.alpha * (double)a.alpha;
   const double m2 = (double)a.M * (double)a.M;
   const double cc = 1.0 / (a2 * m2);
-  const double err = E2 + a.sc.Ehat2[m];
+  const double err = E2 + ehat2;
   const double t1 = cc * Hsum;
   const double t2 = 3.0 * err;
   const double rhs = t1 + t2;
-  bool skip = (a.sc.t[m] < a.t_bar) && (lhs <= rhs);
+  bool skip = (t_m < a.t_bar) && (lhs <= rhs);
   if (a.mode & LAQ_MODE_FORCE_UPLOAD) skip = false;
   if (!finite) { skip = true; atomicOr(a.sc.status, 1u); }
   a.upload[m] = skip ? 0 : 1;
@@ -315,6 +316,16 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     const int sh = a.eps_K - c.x;
     double accN = 0.0;
     unsigned long long accS = 0;
+    // one block per worker: it applies the skip rule itself; what the rule needs is fetched now,
+    // long before it is used
+    const bool solo = a.fused_decide && gridDim.x == 1;
+    __shared__ double hterm_s[kMaxHistLds];
+    double ehat2 = 0.0;
+    int t_m = 0;
+    if (solo) {
+      stage_history(a, hterm_s);
+      if (threadIdx.x == 0) { ehat2 = a.sc.Ehat2[m]; t_m = a.sc.t[m]; }
+    }
 
     if (c.zero) {
       for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads)
@@ -355,11 +366,23 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
     __syncthreads();
     __shared__ bool last_s;
+    if (solo) {
+      if (threadIdx.x == 0) {
+        constexpr int L = (1 << B) - 1;
+        const unsigned long long Sq = (smS[0] + smS[1]) + (smS[2] + smS[3]);
+        const unsigned long long N = (smN[0] + smN[1]) + (smN[2] + smN[3]);
+        const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
+        const double r = (double)c.R / (double)L;
+        const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
+        apply_skip_rule(a, m, c.R, c.finite, lhs, E2, c.zero ? 0 : (long long)Sq, hterm_s, ehat2, t_m);
+      }
+      return;
+    }
     if (threadIdx.x == 0) {
       const int64_t slot = (int64_t)m * a.slots + blockIdx.x;
       a.sc.Spart[slot] = (smS[0] + smS[1]) + (smS[2] + smS[3]);
       a.sc.Npart[slot] = (smN[0] + smN[1]) + (smN[2] + smN[3]);
-      if (a.fused_decide && gridDim.x > 1) {
+      if (a.fused_decide) {
         // few blocks per worker: the last one to finish applies the skip rule
         // (saves a launch; with thousands of blocks the counter would serialise)
         __threadfence();
@@ -368,9 +391,7 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     }
     if (a.fused_decide) {
       __syncthreads();
-      if (gridDim.x == 1) {
-        decide_worker<B>(a, m, 1);            // one block per worker: its own partials, no hand-over
-      } else if (last_s) {
+      if (last_s) {
         __threadfence();
         if (threadIdx.x == 0) a.sc.ticket[m] = 0;
         decide_worker<B>(a, m, (int32_t)gridDim.x);
@@ -411,7 +432,7 @@ __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t
   const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
   const double r = (double)c.R / (double)L;
   const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
-  apply_skip_rule(a, m, c.R, c.finite, lhs, E2, c.zero ? 0 : (long long)Sq, hterm);
+  apply_skip_rule(a, m, c.R, c.finite, lhs, E2, c.zero ? 0 : (long long)Sq, hterm, a.sc.Ehat2[m], a.sc.t[m]);
 }
 
 template <int B>
@@ -497,7 +518,7 @@ __global__ __launch_bounds__(kThreads) void exact_decide_kernel(QuantArgs a, int
   }
   if (threadIdx.x != 0) return;
   const QuantConst c = quant_const<kExact>(max(max(smR[0], smR[1]), max(smR[2], smR[3])));
-  apply_skip_rule(a, m, c.R, c.finite, c.finite ? red[0] : 0.0, 0.0, 0, hterm);
+  apply_skip_rule(a, m, c.R, c.finite, c.finite ? red[0] : 0.0, 0.0, 0, hterm, a.sc.Ehat2[m], a.sc.t[m]);
 }
 
 // ------------------------------------------------------------------ server step
@@ -516,8 +537,35 @@ struct ServerArgs {
   float alpha;
 };
 
+// First chunk (index threadIdx.x) of every array the bookkeeping reads, fetched in one go so that
+// the block pays one memory latency for them, not one per array.
+struct FinishFetch {
+  double e2, part, older;
+  unsigned long long n_uploads;
+  int32_t t;
+  uint8_t up;
+};
+
+// own_total: the sum of ||nabla||^2 when the calling block is the whole grid (then no partial is read)
+__device__ __forceinline__ FinishFetch finish_fetch(const ServerArgs& a, int n_blocks, bool own_total) {
+  FinishFetch f;
+  const int m = threadIdx.x;
+  const bool have = m < a.M;
+  f.up = have ? a.upload[m] : (uint8_t)0;
+  f.e2 = have ? a.sc.E2[m] : 0.0;
+  f.t = have ? a.sc.t[m] : 0;
+  f.n_uploads = have ? a.sc.uploads[m] : 0ull;
+  f.part = (!own_total && m < n_blocks)
+               ? __hip_atomic_load(&a.sc.srv_part[m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+               : 0.0;
+  const int d = a.D - 1 - m;
+  f.older = d >= 1 ? a.sc.dtheta2[d - 1] : 0.0;
+  return f;
+}
+
 template <int B>
-__device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks);
+__device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks, const FinishFetch& f,
+                                              const double* own_total);
 
 constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
 
@@ -527,7 +575,10 @@ constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
 // kernel and keeps their running sums in registers, so the grid sweeps one
 // uploading worker's row at a time (one read stream, one write stream) in
 // ascending m -- the order in which the sums are defined.
-template <int B>
+// SOLO: the grid is this one block. It then fetches nabla, theta and what the bookkeeping reads
+// at the start, so that a call on a small model pays for three dependent memory round trips
+// (upload flags, message rows, stores) instead of seven.
+template <int B, bool SOLO>
 __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   constexpr uint32_t L = B >= 32 ? 0xffffffffu : (1u << (B & 31)) - 1u;
   extern __shared__ unsigned char smem_raw[];
@@ -535,6 +586,24 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   float* Rm = reinterpret_cast<float*>(list + a.M);               // [M]
   float* stepm = Rm + a.M;                                        // [M]
   __shared__ int n_up_s;
+
+  const int64_t nfull = a.p / kGroup;
+  const int64_t span = (int64_t)gridDim.x * kThreads;
+  const int64_t grp0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  float4 pn[kServerJ][2], pt[kServerJ][2];
+  FinishFetch ff;
+  if constexpr (SOLO) {
+    ff = finish_fetch(a, 1, true);
+#pragma unroll
+    for (int j = 0; j < kServerJ; ++j) {
+      const int64_t grp = grp0 + j * span;
+      if (j < a.J && grp < nfull) {
+        const float4* np4 = reinterpret_cast<const float4*>(a.nabla + grp * kGroup);
+        const float4* tp4 = reinterpret_cast<const float4*>(a.theta + grp * kGroup);
+        pn[j][0] = np4[0]; pn[j][1] = np4[1]; pt[j][0] = tp4[0]; pt[j][1] = tp4[1];
+      }
+    }
+  }
 
   // ascending list of workers whose message carries a non-zero innovation
   // (order-preserving compaction: wavefront ballots + prefix counts)
@@ -563,15 +632,11 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   }
   const int n_up = n_up_s;
 
-  const int64_t nfull = a.p / kGroup;
-  const int64_t span = (int64_t)gridDim.x * kThreads;
-  const int64_t grp0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   float acc[kServerJ][kGroup];
 #pragma unroll
   for (int j = 0; j < kServerJ; ++j)
 #pragma unroll
     for (int i = 0; i < kGroup; ++i) acc[j][i] = 0.0f;
-
   for (int k = 0; k < n_up; ++k) {
     const int m = list[k];
     const float R = Rm[m], step = stepm[m];
@@ -618,7 +683,12 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
     if (j < a.J && grp < nfull) {
       float4* np4 = reinterpret_cast<float4*>(a.nabla + grp * kGroup);
       float4* tp4 = reinterpret_cast<float4*>(a.theta + grp * kGroup);
-      const float4 n0 = np4[0], n1 = np4[1], t0 = tp4[0], t1 = tp4[1];
+      float4 n0, n1, t0, t1;
+      if constexpr (SOLO) {
+        n0 = pn[j][0]; n1 = pn[j][1]; t0 = pt[j][0]; t1 = pt[j][1];
+      } else {
+        n0 = np4[0]; n1 = np4[1]; t0 = tp4[0]; t1 = tp4[1];
+      }
       float nv[8] = {n0.x, n0.y, n0.z, n0.w, n1.x, n1.y, n1.z, n1.w};
       float tv[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
 #pragma unroll
@@ -670,44 +740,67 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   __shared__ bool last_s;
   if ((threadIdx.x & 63) == 0) smd[threadIdx.x >> 6] = n2;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
-    if (a.fused_finish && gridDim.x > 1) {
-      __threadfence();
-      last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
+  if constexpr (SOLO) {
+    __shared__ double total_s;
+    if (threadIdx.x == 0) total_s = (smd[0] + smd[1]) + (smd[2] + smd[3]);
+    __syncthreads();
+    server_finish<B>(a, 1, ff, &total_s);
+  } else {
+    if (threadIdx.x == 0) {
+      a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
+      if (a.fused_finish) {
+        __threadfence();
+        last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
+      }
     }
-  }
-  if (!a.fused_finish) return;      // large grids: a follow-up kernel finishes (no fences here)
-  __syncthreads();
-  if (gridDim.x > 1) {
+    if (!a.fused_finish) return;      // large grids: a follow-up kernel finishes (no fences here)
+    __syncthreads();
     if (!last_s) return;
     __threadfence();
     if (threadIdx.x == 0) *a.sc.srv_ticket = 0;
+    server_finish<B>(a, (int)gridDim.x, finish_fetch(a, (int)gridDim.x, false), nullptr);
   }
-  server_finish<B>(a, (int)gridDim.x);
 }
 
 // Bookkeeping of Algorithm 2 (clocks, error norms, counters) and the new entry
 // alpha^2 ||nabla||^2 of the parameter-difference history; run by one block.
 template <int B>
-__device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks) {
+__device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks, const FinishFetch& f,
+                                              const double* own_total) {
   __shared__ double red[kThreads];
   unsigned long long my_bits = 0;
-  for (int m = threadIdx.x; m < a.M; m += kThreads) {
+  const unsigned long long msg_bits = (B == kExact ? 0ull : 32ull) + (unsigned long long)B * (unsigned long long)a.p;
+  if ((int)threadIdx.x < a.M) {                       // first chunk: already fetched
+    const int m = threadIdx.x;
+    if (f.up) {
+      a.sc.Ehat2[m] = f.e2;
+      a.sc.t[m] = 0;
+      a.sc.uploads[m] = f.n_uploads + 1;
+      my_bits += msg_bits;
+    } else {
+      a.sc.t[m] = f.t + 1;
+    }
+  }
+  for (int m = threadIdx.x + kThreads; m < a.M; m += kThreads) {
     if (a.upload[m]) {
       a.sc.Ehat2[m] = a.sc.E2[m];
       a.sc.t[m] = 0;
       a.sc.uploads[m] += 1;
-      my_bits += (B == kExact ? 0ull : 32ull) + (unsigned long long)B * (unsigned long long)a.p;
+      my_bits += msg_bits;
     } else {
       a.sc.t[m] += 1;
     }
   }
   if (my_bits) atomicAdd(a.sc.bits, my_bits);
   // ||nabla||^2: block partials summed in a fixed order (strided, then a tree)
-  double tot = 0.0;
-  for (int i = threadIdx.x; i < n_blocks; i += kThreads)
-    tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  double tot;
+  if (own_total) {
+    tot = threadIdx.x == 0 ? *own_total : 0.0;
+  } else {
+    tot = f.part;
+    for (int i = threadIdx.x + kThreads; i < n_blocks; i += kThreads)
+      tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   red[threadIdx.x] = tot;
   __syncthreads();
   for (int off = kThreads / 2; off > 0; off >>= 1) {
@@ -716,10 +809,13 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks)
   }
   // history shift: all entries are read before any is written (one memory latency, not D)
   const double newest = ((double)a.alpha * (double)a.alpha) * red[0];
+  bool first = true;
   for (int base = a.D - 1; base >= 0; base -= kThreads) {        // highest chunk first
     const int d = base - (int)threadIdx.x;                       // this thread's destination
     double v = 0.0;
-    if (d >= 1) v = a.sc.dtheta2[d - 1];
+    if (first) v = f.older;                                      // fetched before anything was written
+    else if (d >= 1) v = a.sc.dtheta2[d - 1];
+    first = false;
     __syncthreads();
     if (d >= 1) a.sc.dtheta2[d] = v;
     else if (d == 0) a.sc.dtheta2[0] = newest;
@@ -729,7 +825,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks)
 
 template <int B>
 __global__ __launch_bounds__(kThreads) void server_finish_kernel(ServerArgs a, int n_blocks) {
-  server_finish<B>(a, n_blocks);
+  server_finish<B>(a, n_blocks, finish_fetch(a, n_blocks, false), nullptr);
 }
 
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
@@ -829,7 +925,11 @@ static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
 }
 template <int B>
 static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArgs& a) {
-  hipLaunchKernelGGL(server_kernel<B>, grid, dim3(kThreads), smem, s, a);
+  if (grid.x == 1) {
+    hipLaunchKernelGGL((server_kernel<B, true>), grid, dim3(kThreads), smem, s, a);
+    return;
+  }
+  hipLaunchKernelGGL((server_kernel<B, false>), grid, dim3(kThreads), smem, s, a);
   if (!a.fused_finish)
     hipLaunchKernelGGL(server_finish_kernel<B>, dim3(1), dim3(kThreads), 0, s, a, (int)grid.x);
 }

@@ -603,15 +603,24 @@ static int gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch) {
 
 
 // Weight-gradient GEMMs whose 128 x 128 tiles would leave most CUs idle (narrow layers) split the
-// sample dimension: nsplit partial products per worker, summed by slab_finish_kernel.
+// sample dimension: nsplit partial products per worker, summed by slab_finish_kernel.  All blocks
+// of such a launch are resident at once (at most four per CU), so the launch takes as long as the
+// fullest CU: nsplit is the value whose block count fills whole rounds of CUs best.
 static int dw_splits(const laq_ctx* ctx, int64_t in, int64_t out, int64_t N_m) {
   const int64_t blocks128 = ((in + 127) / 128) * ((out + 127) / 128) * ctx->M;
   if (blocks128 >= (int64_t)ctx->n_cu * 3) return 1;
-  int64_t ns = ((int64_t)ctx->n_cu * 2 + blocks128 - 1) / blocks128;
-  const int64_t max_by_k = N_m / 512;          // at least 512 samples per split
-  if (ns > max_by_k) ns = max_by_k;
-  if (ns > 16) ns = 16;
-  return ns < 2 ? 1 : (int)ns;
+  int64_t max_ns = N_m / 512;                  // at least 512 samples per split
+  if (max_ns > 16) max_ns = 16;
+  int best = 1;
+  double best_fill = 0.0;
+  for (int64_t ns = 2; ns <= max_ns; ++ns) {
+    const int64_t blocks = blocks128 * ns;
+    if (blocks > (int64_t)ctx->n_cu * 4) break;
+    const int64_t rounds = (blocks + ctx->n_cu - 1) / ctx->n_cu;
+    const double fill = (double)blocks / (double)(rounds * ctx->n_cu);
+    if (fill > best_fill + 0.02) { best_fill = fill; best = (int)ns; }   // near-ties: fewer partials
+  }
+  return best;
 }
 
 struct MlpPlan {

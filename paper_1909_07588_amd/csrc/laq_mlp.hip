@@ -44,21 +44,41 @@ struct GemmArgs {
   int32_t nsplit, ksplit;
 };
 
-// Tile loaders.  A block tile is BT = 64 NL wide and BK deep; each lane moves
-// NV = NL BK / 16 float4 per operand.  LDS tiles are K-major: tile[kk][xx].
+// Tile loaders.  An operand's block tile is BX wide and BK deep, BX BK / 4 float4 in all: lane t
+// moves the float4 numbered e = t + 256 i, i < NV = ceil(BX BK / 1024); when BX BK is not a
+// multiple of 1024 the last of them does not exist for some lanes.  LDS tiles are K-major: tile[kk][xx].
+template <int BX, int BK>
+struct TileMap {
+  static constexpr int kVec = BX * BK / 4;                       // float4 per tile
+  static constexpr int NV = (kVec + kThreads - 1) / kThreads;
+  static constexpr bool kExact = (kVec % kThreads) == 0;
+  static constexpr int TPR = BX / 4;                             // lanes per tile row (K-major source)
+  static constexpr int LPR = BK / 4;                             // lanes per source row (X-major source)
+  __device__ static __forceinline__ bool exists(int i) { return kExact || (int)threadIdx.x + kThreads * i < kVec; }
+  // K-major source S[k][x]: float4 e covers tile[kk][xx .. xx+3]
+  __device__ static __forceinline__ void kmajor(int i, int& kk, int& xx) {
+    const int e = (int)threadIdx.x + kThreads * i;
+    kk = e / TPR; xx = (e % TPR) * 4;
+  }
+  // X-major source S[x][k]: float4 e covers tile[kk .. kk+3][xx]
+  __device__ static __forceinline__ void xmajor(int i, int& kk, int& xx) {
+    const int e = (int)threadIdx.x + kThreads * i;
+    xx = e / LPR; kk = (e % LPR) * 4;
+  }
+};
 
 // K-major source S[k][x]
-template <int NL, int BK>
+template <int BX, int BK>
 __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, int X, int k0, int x0,
-                                            int vec, float4 (&r)[NL * BK / 16]) {
-  const int t = threadIdx.x;
-  constexpr int TPR = 16 * NL;          // lanes per tile row
+                                            int vec, float4 (&r)[TileMap<BX, BK>::NV]) {
+  using TM = TileMap<BX, BK>;
 #pragma unroll
-  for (int i = 0; i < NL * BK / 16; ++i) {
-    const int kk = t / TPR + (kThreads / TPR) * i, xx = (t % TPR) * 4;
+  for (int i = 0; i < TM::NV; ++i) {
+    int kk, xx;
+    TM::kmajor(i, kk, xx);
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (k < K) {
+    if (TM::exists(i) && k < K) {
       const float* src = S + (int64_t)k * ld + x;
       if (vec && x + 3 < X) {
         v = *reinterpret_cast<const float4*>(src);
@@ -72,29 +92,29 @@ __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, i
     r[i] = v;
   }
 }
-template <int NL, int BK>
-__device__ __forceinline__ void store_direct(float (*tile)[64 * NL + 4], const float4 (&r)[NL * BK / 16]) {
-  const int t = threadIdx.x;
-  constexpr int TPR = 16 * NL;
+template <int BX, int BK>
+__device__ __forceinline__ void store_direct(float (*tile)[BX + 4], const float4 (&r)[TileMap<BX, BK>::NV]) {
+  using TM = TileMap<BX, BK>;
 #pragma unroll
-  for (int i = 0; i < NL * BK / 16; ++i) {
-    const int kk = t / TPR + (kThreads / TPR) * i, xx = (t % TPR) * 4;
-    *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
+  for (int i = 0; i < TM::NV; ++i) {
+    int kk, xx;
+    TM::kmajor(i, kk, xx);
+    if (TM::exists(i)) *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
   }
 }
 
 // X-major source S[x][k] (transposed on the way into LDS)
-template <int NL, int BK>
+template <int BX, int BK>
 __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int K, int X, int k0, int x0,
-                                                int vec, float4 (&r)[NL * BK / 16]) {
-  const int t = threadIdx.x;
-  constexpr int LPR = BK / 4;           // lanes per source row
+                                                int vec, float4 (&r)[TileMap<BX, BK>::NV]) {
+  using TM = TileMap<BX, BK>;
 #pragma unroll
-  for (int i = 0; i < NL * BK / 16; ++i) {
-    const int xx = t / LPR + (kThreads / LPR) * i, kk = (t % LPR) * 4;
+  for (int i = 0; i < TM::NV; ++i) {
+    int kk, xx;
+    TM::xmajor(i, kk, xx);
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (x < X) {
+    if (TM::exists(i) && x < X) {
       const float* src = S + (int64_t)x * ld + k;
       if (vec && k + 3 < K) {
         v = *reinterpret_cast<const float4*>(src);
@@ -108,17 +128,19 @@ __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int 
     r[i] = v;
   }
 }
-template <int NL, int BK>
-__device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], const float4 (&r)[NL * BK / 16]) {
-  const int t = threadIdx.x;
-  constexpr int LPR = BK / 4;
+template <int BX, int BK>
+__device__ __forceinline__ void store_transposed(float (*tile)[BX + 4], const float4 (&r)[TileMap<BX, BK>::NV]) {
+  using TM = TileMap<BX, BK>;
 #pragma unroll
-  for (int i = 0; i < NL * BK / 16; ++i) {
-    const int xx = t / LPR + (kThreads / LPR) * i, kk = (t % LPR) * 4;
-    tile[kk + 0][xx] = r[i].x;
-    tile[kk + 1][xx] = r[i].y;
-    tile[kk + 2][xx] = r[i].z;
-    tile[kk + 3][xx] = r[i].w;
+  for (int i = 0; i < TM::NV; ++i) {
+    int kk, xx;
+    TM::xmajor(i, kk, xx);
+    if (TM::exists(i)) {
+      tile[kk + 0][xx] = r[i].x;
+      tile[kk + 1][xx] = r[i].y;
+      tile[kk + 2][xx] = r[i].z;
+      tile[kk + 3][xx] = r[i].w;
+    }
   }
 }
 
@@ -126,33 +148,28 @@ __device__ __forceinline__ void store_transposed(float (*tile)[64 * NL + 4], con
 // is wholly inside or wholly outside the operand, so a lane keeps one clamped
 // source pointer per float4, loads unconditionally and zeroes what lies outside.
 // No branch sits between the loads and the matrix instructions they overlap.
-template <int NL, int BK, bool XMAJOR>
+template <int BX, int BK, bool XMAJOR>
 struct FastLoader {
-  static constexpr int NV = NL * BK / 16;
+  using TM = TileMap<BX, BK>;
+  static constexpr int NV = TM::NV;
   const float* q[NV];   // source address of this lane's float4 in the next K tile to load (clamped into the operand)
   int kk[NV];           // its k offset inside the tile
-  bool xin[NV];         // its row/column lies inside the operand
+  bool xin[NV];         // its row/column lies inside the operand (false for a float4 that does not exist)
   int64_t kstep;        // address advance per K tile
   int K;
   bool all_in;          // the whole block tile lies inside the operand (uniform over the block)
 
   __device__ __forceinline__ void init(const float* S, int64_t ld, int K_, int X, int x0) {
-    const int t = threadIdx.x;
     K = K_;
-    all_in = x0 + 64 * NL <= X;
+    all_in = TM::kExact && x0 + BX <= X;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       int kq, xx;
-      if (XMAJOR) {
-        constexpr int LPR = BK / 4;
-        xx = t / LPR + (kThreads / LPR) * i; kq = (t % LPR) * 4;
-      } else {
-        constexpr int TPR = 16 * NL;
-        kq = t / TPR + (kThreads / TPR) * i; xx = (t % TPR) * 4;
-      }
+      if (XMAJOR) TM::xmajor(i, kq, xx); else TM::kmajor(i, kq, xx);
+      if (!TM::exists(i)) { kq = 0; xx = 0; }
       kk[i] = kq;
       const int x = x0 + xx;
-      xin[i] = x < X;
+      xin[i] = TM::exists(i) && x < X;
       const int xc = xin[i] ? x : 0;
       q[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
     }
@@ -197,21 +214,21 @@ struct FastLoader {
 #ifndef LAQ_GEMM_NBUF
 #define LAQ_GEMM_NBUF 2
 #endif
-// four wavefronts per SIMD: 64 accumulator registers + at most 64 others
-#ifndef LAQ_GEMM_OCC
-#define LAQ_GEMM_OCC __attribute__((amdgpu_waves_per_eu(4, 4)))
-#endif
 
-// C = op(A) op(B) with a fused epilogue.  NBUF = 2: the next K tile is written to
-// the other LDS buffer while the current one is multiplied (one barrier per tile).
-template <bool TA, bool TB, int EPI, int NL, bool FAST>
-__global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g) {
+// C = op(A) op(B) with a fused epilogue.  Four wavefronts in WM rows and 4 / WM columns, each
+// with NLM x NLN matrix-instruction tiles of 32 x 32: block tile 32 WM NLM x 32 WN NLN.
+// NBUF = 2: the next K tile is written to the other LDS buffer while the current one is
+// multiplied (one barrier per tile).
+template <bool TA, bool TB, int EPI, int WM, int NLM, int NLN, bool FAST>
+__device__ __forceinline__ void gemm_body(GemmArgs g) {
   constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
-  constexpr int BT = 64 * NL, kLd = BT + 4, WT = 32 * NL;   // block tile, LDS row stride, wave tile
-  constexpr int kBM = BT, kBN = BT, NV = NL * BK / 16;
+  constexpr int WN = 4 / WM;
+  constexpr int kBM = 32 * WM * NLM, kBN = 32 * WN * NLN;
+  constexpr int kLdA = kBM + 4, kLdB = kBN + 4;               // LDS row strides
+  constexpr int NVA = TileMap<kBM, BK>::NV, NVB = TileMap<kBN, BK>::NV;
   extern __shared__ __attribute__((aligned(16))) float gemm_smem[];
-  float (*As)[BK][kLd] = reinterpret_cast<float (*)[BK][kLd]>(gemm_smem);
-  float (*Bs)[BK][kLd] = reinterpret_cast<float (*)[BK][kLd]>(gemm_smem + NBUF * BK * kLd);
+  float (*As)[BK][kLdA] = reinterpret_cast<float (*)[BK][kLdA]>(gemm_smem);
+  float (*Bs)[BK][kLdB] = reinterpret_cast<float (*)[BK][kLdB]>(gemm_smem + NBUF * BK * kLdA);
   const float* A = g.A;
   const float* B = g.B;
   if (EPI == EPI_PARTIAL) {
@@ -227,19 +244,19 @@ __global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g)
   float* C = g.C + (int64_t)blockIdx.z * g.sC;
   const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wy = wave >> 1, wx = wave & 1;
+  const int wy = wave / WN, wx = wave % WN;
 
-  floatx16 acc[NL][NL];
+  floatx16 acc[NLM][NLN];
 #pragma unroll
-  for (int i = 0; i < NL; ++i)
+  for (int i = 0; i < NLM; ++i)
 #pragma unroll
-    for (int j = 0; j < NL; ++j)
+    for (int j = 0; j < NLN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  float4 ra[NV], rb[NV];
-  FastLoader<NL, BK, !TA> fa;   // A is [M][K] (row-major in M) unless TA
-  FastLoader<NL, BK, TB> fb;    // B is [N][K] only if TB
+  float4 ra[NVA], rb[NVB];
+  FastLoader<kBM, BK, !TA> fa;   // A is [M][K] (row-major in M) unless TA
+  FastLoader<kBN, BK, TB> fb;    // B is [N][K] only if TB
   if (FAST) {
     fa.init(A, g.lda, g.K, g.M, m0);
     fb.init(B, g.ldb, g.K, g.N, n0);
@@ -250,18 +267,18 @@ __global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g)
       fb.load(k0 / BK, rb);
       return;
     }
-    if (TA) load_direct<NL, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    else load_transposed<NL, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    if (TB) load_transposed<NL, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
-    else load_direct<NL, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    if (TA) load_direct<kBM, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    else load_transposed<kBM, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
+    if (TB) load_transposed<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    else load_direct<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
   };
   auto stage = [&](int buf, int k0) {
     if (FAST) {
       fa.mask(k0 / BK, ra);
       fb.mask(k0 / BK, rb);
     }
-    if (TA) store_direct<NL, BK>(As[buf], ra); else store_transposed<NL, BK>(As[buf], ra);
-    if (TB) store_transposed<NL, BK>(Bs[buf], rb); else store_direct<NL, BK>(Bs[buf], rb);
+    if (TA) store_direct<kBM, BK>(As[buf], ra); else store_transposed<kBM, BK>(As[buf], ra);
+    if (TB) store_transposed<kBN, BK>(Bs[buf], rb); else store_direct<kBN, BK>(Bs[buf], rb);
   };
 
   fetch(0);
@@ -274,16 +291,15 @@ __global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g)
     if (more) fetch(k0 + BK);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float av[NL], bv[NL];
+      float av[NLM], bv[NLN];
 #pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        av[i] = As[cur][kk + kh][wy * WT + 32 * i + li];
-        bv[i] = Bs[cur][kk + kh][wx * WT + 32 * i + li];
-      }
+      for (int i = 0; i < NLM; ++i) av[i] = As[cur][kk + kh][(wy * NLM + i) * 32 + li];
 #pragma unroll
-      for (int i = 0; i < NL; ++i)
+      for (int j = 0; j < NLN; ++j) bv[j] = Bs[cur][kk + kh][(wx * NLN + j) * 32 + li];
 #pragma unroll
-        for (int j = 0; j < NL; ++j)
+      for (int i = 0; i < NLM; ++i)
+#pragma unroll
+        for (int j = 0; j < NLN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
     }
     if (NBUF == 2) {
@@ -304,16 +320,16 @@ __global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g)
   uint32_t dmax = 0;
   const float* Hq = (EPI == EPI_GRAD) ? g.Hq + (int64_t)blockIdx.z * g.sC : nullptr;
 #pragma unroll
-  for (int ti = 0; ti < NL; ++ti)
+  for (int ti = 0; ti < NLM; ++ti)
 #pragma unroll
-    for (int tj = 0; tj < NL; ++tj) {
-      const int col = n0 + wx * WT + tj * 32 + li;
+    for (int tj = 0; tj < NLN; ++tj) {
+      const int col = n0 + (wx * NLN + tj) * 32 + li;
       if (col >= g.N) continue;
       float bias = 0.0f;
       if (EPI == EPI_BIAS_RELU) bias = g.aux[col];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wy * WT + ti * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+        const int row = m0 + (wy * NLM + ti) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
         if (row >= g.M) continue;
         float v = acc[ti][tj][r];
         if (EPI == EPI_BIAS_RELU) {
@@ -344,6 +360,21 @@ __global__ __launch_bounds__(kThreads) LAQ_GEMM_OCC void gemm_kernel(GemmArgs g)
       g.rprod[(int64_t)blockIdx.z * g.rstride + g.rbase + blockIdx.y * gridDim.x + blockIdx.x] =
           max(max(red[0], red[1]), max(red[2], red[3]));
   }
+}
+
+// Square block tiles of 64 NL: 2 x 2 wavefronts.  Four wavefronts per SIMD: 64 accumulator
+// registers + at most 64 others.
+template <bool TA, bool TB, int EPI, int NL, bool FAST>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_kernel(GemmArgs g) {
+  gemm_body<TA, TB, EPI, 2, NL, NL, FAST>(g);
+}
+
+// Layers between 129 and 224 units wide: one 128 x 32 NLN block tile spans the whole width
+// (a 128 x 128 tiling would spend a second, mostly empty tile column on it).  Each wavefront
+// owns 32 rows and all NLN column tiles; two wavefronts per SIMD.
+template <bool TA, bool TB, int EPI, int NLN, bool FAST>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_wide_kernel(GemmArgs g) {
+  gemm_body<TA, TB, EPI, 4, 1, NLN, FAST>(g);
 }
 
 // ------------------------------------------------------------------ class layer (C <= 16)
@@ -549,7 +580,16 @@ __global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __re
   if (j < len) {
     const float* pm = part + (int64_t)m * n_slab * len;
     float s = 0.0f;
-    for (int k = 0; k < n_slab; ++k) s += pm[(int64_t)k * len + j];
+    int k = 0;
+    // eight partials in flight, added in ascending order (one memory latency per eight, not per one)
+    for (; k + 8 <= n_slab; k += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = pm[(int64_t)(k + u) * len + j];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; k < n_slab; ++k) s += pm[(int64_t)k * len + j];
     const float gv = fmaf(s, scale, reg * theta_seg[j]);
     G[(int64_t)m * p_stride + j] = gv;
     mx = __float_as_uint(gv - Hq[(int64_t)m * p_stride + j]) & 0x7fffffffu;
@@ -595,26 +635,33 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(const float* __restric
 
 static inline int64_t align_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
-// Block tile: 128 x 128 when that still gives every CU a few blocks, else 64 x 64.
-static int gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch) {
+struct GemmTile { int bm, bn; };
+
+// Block tile: 128 x 128 when that still gives every CU a few blocks, else 64 x 64; 128 x (160, 192
+// or 224) for an output 129..224 columns wide with enough rows of tiles to occupy the chip.
+// big: the caller fills the chip by other means (split K) and wants the large tiles.
+static GemmTile gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch, bool big = false) {
+  if (Nc > 128 && Nc <= 224 && (big || ((Mr + 127) / 128) * batch >= (int64_t)ctx->n_cu))
+    return GemmTile{128, (int)((Nc + 31) / 32 * 32)};
   const int64_t blocks128 = ((Mr + 127) / 128) * ((Nc + 127) / 128) * batch;
-  return blocks128 >= (int64_t)ctx->n_cu * 3 ? 128 : 64;
+  const int bt = (big || blocks128 >= (int64_t)ctx->n_cu * 3) ? 128 : 64;
+  return GemmTile{bt, bt};
 }
 
-
-// Weight-gradient GEMMs whose 128 x 128 tiles would leave most CUs idle (narrow layers) split the
+// Weight-gradient GEMMs whose large tiles would leave most CUs idle (narrow layers) split the
 // sample dimension: nsplit partial products per worker, summed by slab_finish_kernel.  All blocks
-// of such a launch are resident at once (at most four per CU), so the launch takes as long as the
+// of such a launch are resident at once or nearly so, so the launch takes as long as the
 // fullest CU: nsplit is the value whose block count fills whole rounds of CUs best.
 static int dw_splits(const laq_ctx* ctx, int64_t in, int64_t out, int64_t N_m) {
-  const int64_t blocks128 = ((in + 127) / 128) * ((out + 127) / 128) * ctx->M;
-  if (blocks128 >= (int64_t)ctx->n_cu * 3) return 1;
+  const GemmTile t = gemm_tile(ctx, in, out, ctx->M, true);
+  const int64_t blocks1 = ((in + t.bm - 1) / t.bm) * ((out + t.bn - 1) / t.bn) * ctx->M;
+  if (blocks1 >= (int64_t)ctx->n_cu * 3) return 1;
   int64_t max_ns = N_m / 512;                  // at least 512 samples per split
   if (max_ns > 16) max_ns = 16;
   int best = 1;
   double best_fill = 0.0;
   for (int64_t ns = 2; ns <= max_ns; ++ns) {
-    const int64_t blocks = blocks128 * ns;
+    const int64_t blocks = blocks1 * ns;
     if (blocks > (int64_t)ctx->n_cu * 4) break;
     const int64_t rounds = (blocks + ctx->n_cu - 1) / ctx->n_cu;
     const double fill = (double)blocks / (double)(rounds * ctx->n_cu);
@@ -670,8 +717,8 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
         const int64_t need = (int64_t)ctx->M * ns * in * out;
         splitk = splitk > need ? splitk : need;
       } else {
-        const int bt = gemm_tile(ctx, in, out, ctx->M);
-        cnt += ((out + bt - 1) / bt) * ((in + bt - 1) / bt);
+        const GemmTile t = gemm_tile(ctx, in, out, ctx->M);
+        cnt += ((out + t.bn - 1) / t.bn) * ((in + t.bm - 1) / t.bm);
       }
     }
     else cnt += (in * out + kThreads - 1) / kThreads;                              // class layer
@@ -688,24 +735,33 @@ size_t mlp_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
   return (size_t)make_plan(ctx, N_m).total_floats * sizeof(float) + 256;
 }
 
-static size_t gemm_lds_bytes(int bt) {
-  return (size_t)2 * LAQ_GEMM_NBUF * LAQ_GEMM_BK * (bt + 4) * sizeof(float);
+static size_t gemm_lds_bytes(GemmTile t) {
+  return (size_t)LAQ_GEMM_NBUF * LAQ_GEMM_BK * (t.bm + 4 + t.bn + 4) * sizeof(float);
 }
 
 template <bool TA, bool TB, int EPI>
-static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool force128 = false) {
-  const int bt = force128 ? 128 : gemm_tile(ctx, g.M, g.N, batch);
-  const dim3 grid((unsigned)((g.N + bt - 1) / bt), (unsigned)((g.M + bt - 1) / bt), (unsigned)batch);
+static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool big = false) {
+  const GemmTile t = gemm_tile(ctx, g.M, g.N, batch, big);
+  const dim3 grid((unsigned)((g.N + t.bn - 1) / t.bn), (unsigned)((g.M + t.bm - 1) / t.bm), (unsigned)batch);
   // fast loaders need aligned operand rows and no float4 straddling an operand edge
   const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4;
-  const size_t smem = gemm_lds_bytes(bt);
-  if (bt == 128) {
-    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), grid, dim3(kThreads), smem, ctx->stream, g);
-    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, false>), grid, dim3(kThreads), smem, ctx->stream, g);
+  const size_t smem = gemm_lds_bytes(t);
+#define LAQ_GEMM_LAUNCH(KERNEL, P)                                                                            \
+  do {                                                                                                        \
+    if (fast) hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, true>), grid, dim3(kThreads), smem, ctx->stream, g);  \
+    else hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, false>), grid, dim3(kThreads), smem, ctx->stream, g);      \
+  } while (0)
+  if (t.bn == t.bm) {
+    if (t.bm == 128) LAQ_GEMM_LAUNCH(gemm_kernel, 2);
+    else LAQ_GEMM_LAUNCH(gemm_kernel, 1);
+  } else if (t.bn == 160) {
+    LAQ_GEMM_LAUNCH(gemm_wide_kernel, 5);
+  } else if (t.bn == 192) {
+    LAQ_GEMM_LAUNCH(gemm_wide_kernel, 6);
   } else {
-    if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, true>), grid, dim3(kThreads), smem, ctx->stream, g);
-    else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, false>), grid, dim3(kThreads), smem, ctx->stream, g);
+    LAQ_GEMM_LAUNCH(gemm_wide_kernel, 7);
   }
+#undef LAQ_GEMM_LAUNCH
 }
 
 static inline int vec_ok(const void* p, int64_t ld) { return (((uintptr_t)p & 15) == 0 && (ld & 3) == 0) ? 1 : 0; }
@@ -837,8 +893,8 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
         rbase += (int32_t)wblocks;
       } else {
         launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
-        const int bt = gemm_tile(ctx, g.M, g.N, ctx->M);
-        rbase += ((g.N + bt - 1) / bt) * ((g.M + bt - 1) / bt);
+        const GemmTile t = gemm_tile(ctx, g.M, g.N, ctx->M);
+        rbase += ((g.N + t.bn - 1) / t.bn) * ((g.M + t.bm - 1) / t.bm);
       }
     }
     // db_l(m) = column sums of dZ_l(m)

@@ -457,119 +457,114 @@ __global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __
   }
 }
 
-// dZ_prev[n][i] = (A[n][i] > 0) ? sum_c dZ[n][c] W[i][c] : 0      (K = width of the hidden layer)
-__global__ __launch_bounds__(kThreads) void class_backward_kernel(const float* __restrict__ dZ,
-                                                                  const float* __restrict__ W,
-                                                                  const float* __restrict__ Aact, int64_t lda,
-                                                                  int64_t S, int32_t K, int32_t C,
-                                                                  float* __restrict__ dZprev, int64_t ldo) {
-  // block: 256 consecutive hidden units i and a run of 64 consecutive rows; the residual rows
-  // are staged in LDS (broadcast reads), four rows of activations in flight per step
-  const int i = blockIdx.x * kThreads + threadIdx.x;
-  float w[kCMax];
-#pragma unroll
-  for (int c = 0; c < kCMax; ++c) w[c] = (i < K && c < C) ? W[(int64_t)i * C + c] : 0.0f;
-  constexpr int kChunk = 64;
-  __shared__ __attribute__((aligned(16))) float dzs[kChunk][kCMax];
-  for (int64_t c0 = (int64_t)blockIdx.y * kChunk; c0 < S; c0 += (int64_t)gridDim.y * kChunk) {
-    const int rows = (int)(S - c0 < kChunk ? S - c0 : kChunk);
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < kChunk * kCMax; idx += kThreads) {
-      const int rr = idx / kCMax, c = idx - rr * kCMax;
-      dzs[rr][c] = (rr < rows && c < C) ? dZ[(c0 + rr) * C + c] : 0.0f;
-    }
-    __syncthreads();
-    if (i >= K) continue;
-    int rr = 0;
-    for (; rr + 4 <= rows; rr += 4) {
-      float av[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) av[u] = Aact[(c0 + rr + u) * lda + i];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        float s = 0.0f;
-#pragma unroll
-        for (int c = 0; c < kCMax; ++c)
-          if (c < C) s = fmaf(dzs[rr + u][c], w[c], s);
-        dZprev[(c0 + rr + u) * ldo + i] = av[u] > 0.0f ? s : 0.0f;
-      }
-    }
-    for (; rr < rows; ++rr) {
-      float s = 0.0f;
-#pragma unroll
-      for (int c = 0; c < kCMax; ++c)
-        if (c < C) s = fmaf(dzs[rr][c], w[c], s);
-      dZprev[(c0 + rr) * ldo + i] = Aact[(c0 + rr) * lda + i] > 0.0f ? s : 0.0f;
-    }
-  }
-}
-
-// Weight gradient of the class layer for worker m and row slab blockIdx.y:
-// part[m][slab][i][c] = sum_{n in slab} A[n][i] dZ[n][c]
-__global__ __launch_bounds__(kThreads) void class_wgrad_kernel(const float* __restrict__ Aact, int64_t lda,
-                                                               const float* __restrict__ dZ, int64_t N_m,
+// Everything the class layer's residuals dZ[n][c] produce, for worker m and row slab blockIdx.y, in
+// one pass over the activations A[n][i] of the last hidden layer (K units wide; the inputs if the
+// network has no hidden layer):
+//   weight gradient   part[..][kb + i C + c] = sum_{n in slab} A[n][i] dZ[n][c]
+//   class bias        part[..][kb + K C + c] = sum_{n in slab} dZ[n][c]
+// and, if a hidden layer precedes (has_prev; then kb = K, else kb = 0),
+//   dZ_prev[n][i] = (A[n][i] > 0) ? sum_c dZ[n][c] W[i][c] : 0   and   part[..][i] = sum_{n in slab} dZ_prev[n][i]
+// (the hidden layer's bias gradient).  The three partials sit in parameter order (b_{L-1}, W_L, b_L),
+// so one slab sum finishes that whole stretch of the gradient.  A thread owns unit i; the residual
+// rows of a chunk are staged in LDS (every lane reads the same row: broadcast reads) and eight rows
+// of activations are in flight per step: the activations are streamed once, so the loop lives on
+// memory latency.
+__global__ __launch_bounds__(kThreads) void class_grads_kernel(const float* __restrict__ Aact, int64_t lda,
+                                                               const float* __restrict__ dZ,
+                                                               const float* __restrict__ W, int64_t N_m,
                                                                int32_t K, int32_t C, int32_t rows_per_slab,
-                                                               float* __restrict__ part) {
+                                                               int32_t has_prev, float* __restrict__ dZprev,
+                                                               int64_t ldo, float* __restrict__ part,
+                                                               int64_t part_stride) {
   const int m = blockIdx.z, slab = blockIdx.y;
   const int i = blockIdx.x * kThreads + threadIdx.x;
+  const bool mine = i < K;
   const int64_t r0 = (int64_t)m * N_m + (int64_t)slab * rows_per_slab;
   int64_t r1 = r0 + rows_per_slab;
   const int64_t rend = (int64_t)(m + 1) * N_m;
   if (r1 > rend) r1 = rend;
-  float acc[kCMax];
+  float acc[kCMax], w[kCMax];
 #pragma unroll
-  for (int c = 0; c < kCMax; ++c) acc[c] = 0.0f;
-  // The residual rows of a chunk are staged in LDS (every lane reads the same row: broadcast
-  // reads), and four rows of activations are in flight per step: the activations are streamed
-  // once, so the loop lives on memory latency.
-  constexpr int kChunk = 64;
+  for (int c = 0; c < kCMax; ++c) {
+    acc[c] = 0.0f;
+    w[c] = (has_prev && mine && c < C) ? W[(int64_t)i * C + c] : 0.0f;
+  }
+  float bprev = 0.0f, bclass = 0.0f;
+  const bool sums_class = blockIdx.x == 0 && (int)threadIdx.x < C;
+  constexpr int kChunk = 128, kFly = 8;
   __shared__ __attribute__((aligned(16))) float dzs[kChunk][kCMax];
-  for (int64_t c0 = r0; c0 < r1; c0 += kChunk) {
-    const int rows = (int)(r1 - c0 < kChunk ? r1 - c0 : kChunk);
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < kChunk * kCMax; idx += kThreads) {
-      const int rr = idx / kCMax, c = idx - rr * kCMax;
-      dzs[rr][c] = (rr < rows && c < C) ? dZ[(c0 + rr) * C + c] : 0.0f;
+  const int64_t icl = mine ? i : 0;                     // idle lanes read column 0 and store nothing
+  // rows n .. n+7 of the activations, always fetched (rows past the slab repeat its last row, unused):
+  // a fetch under a branch would make the compiler wait for it on the spot
+  auto fetch = [&](int64_t n, float (&v)[kFly]) {
+#pragma unroll
+    for (int u = 0; u < kFly; ++u) {
+      const int64_t row = n + u < r1 ? n + u : r1 - 1;
+      v[u] = Aact[row * lda + icl];
     }
-    __syncthreads();
-    int rr = 0;
-    for (; rr + 4 <= rows; rr += 4) {
-      float av[4];
+  };
+  float av[kFly], nx[kFly];
+  if (r0 < r1) fetch(r0, av);
+  for (int64_t n = r0; n < r1; n += kFly) {
+    const int rr0 = (int)((n - r0) % kChunk);
+    if (rr0 == 0) {                                     // next chunk of residual rows
+      const int rows = (int)(r1 - n < kChunk ? r1 - n : kChunk);
+      __syncthreads();
+      for (int idx = threadIdx.x; idx < kChunk * kCMax; idx += kThreads) {
+        const int rr = idx / kCMax, c = idx - rr * kCMax;
+        dzs[rr][c] = (rr < rows && c < C) ? dZ[(n + rr) * C + c] : 0.0f;
+      }
+      __syncthreads();
+      if (sums_class)
+        for (int rr = 0; rr < rows; ++rr) bclass += dzs[rr][threadIdx.x];
+    }
+    fetch(n + kFly, nx);                                // the next group, while this one is used
 #pragma unroll
-      for (int u = 0; u < 4; ++u) av[u] = (i < K) ? Aact[(c0 + rr + u) * lda + i] : 0.0f;
+    for (int u = 0; u < kFly; ++u) {
+      if (n + u >= r1) break;
+      const float a = av[u];
+      const int rr = rr0 + u;
+      float sacc = 0.0f;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int c4 = 0; c4 < kCMax; c4 += 4) {
-          if (c4 < C) {
-            const float4 d = *reinterpret_cast<const float4*>(&dzs[rr + u][c4]);
-            acc[c4] = fmaf(av[u], d.x, acc[c4]);
-            acc[c4 + 1] = fmaf(av[u], d.y, acc[c4 + 1]);
-            acc[c4 + 2] = fmaf(av[u], d.z, acc[c4 + 2]);
-            acc[c4 + 3] = fmaf(av[u], d.w, acc[c4 + 3]);
-          }
+      for (int c4 = 0; c4 < kCMax; c4 += 4) {
+        if (c4 < C) {
+          const float4 d = *reinterpret_cast<const float4*>(&dzs[rr][c4]);
+          acc[c4] = fmaf(a, d.x, acc[c4]);
+          acc[c4 + 1] = fmaf(a, d.y, acc[c4 + 1]);
+          acc[c4 + 2] = fmaf(a, d.z, acc[c4 + 2]);
+          acc[c4 + 3] = fmaf(a, d.w, acc[c4 + 3]);
+          sacc = fmaf(d.x, w[c4], sacc);
+          sacc = fmaf(d.y, w[c4 + 1], sacc);
+          sacc = fmaf(d.z, w[c4 + 2], sacc);
+          sacc = fmaf(d.w, w[c4 + 3], sacc);
         }
       }
+      if (has_prev) {
+        const float o = a > 0.0f ? sacc : 0.0f;
+        if (mine) dZprev[(n + u) * ldo + i] = o;
+        bprev += o;
+      }
     }
-    for (; rr < rows; ++rr) {
-      const float av = (i < K) ? Aact[(c0 + rr) * lda + i] : 0.0f;
 #pragma unroll
-      for (int c = 0; c < kCMax; ++c)
-        if (c < C) acc[c] = fmaf(av, dzs[rr][c], acc[c]);
-    }
+    for (int u = 0; u < kFly; ++u) av[u] = nx[u];
   }
-  if (i < K) {
-    float* out = part + (((int64_t)m * gridDim.y + slab) * K + i) * C;
+  float* out = part + ((int64_t)m * gridDim.y + slab) * part_stride;
+  const int64_t kb = has_prev ? K : 0;
+  if (mine) {
+    if (has_prev) out[i] = bprev;
 #pragma unroll
     for (int c = 0; c < kCMax; ++c)
-      if (c < C) out[c] = acc[c];
+      if (c < C) out[kb + (int64_t)i * C + c] = acc[c];
   }
+  if (sums_class) out[kb + (int64_t)K * C + threadIdx.x] = bclass;
 }
 
-// G[m][off + j] = (sum over slabs, ascending) part[m][slab][j] * scale + reg * theta[off + j]
+// G[m][off + j] = (sum over slabs, ascending) part[m][slab][j] * scale + reg * theta[off + j],
+// part rows `stride` floats apart.
 // Also leaves the block maximum of |G - H| (raw bits) in rprod[m * rstride + rbase + blockIdx.x].
 __global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __restrict__ part, int32_t n_slab,
-                                                               int64_t len, const float* __restrict__ theta_seg,
+                                                               int64_t len, int64_t stride,
+                                                               const float* __restrict__ theta_seg,
                                                                float scale, float reg, float* __restrict__ G,
                                                                const float* __restrict__ Hq, int64_t p_stride,
                                                                uint32_t* __restrict__ rprod, int32_t rstride,
@@ -578,18 +573,21 @@ __global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __re
   const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   uint32_t mx = 0;
   if (j < len) {
-    const float* pm = part + (int64_t)m * n_slab * len;
+    const float* pm = part + (int64_t)m * n_slab * stride;
     float s = 0.0f;
-    int k = 0;
-    // eight partials in flight, added in ascending order (one memory latency per eight, not per one)
-    for (; k + 8 <= n_slab; k += 8) {
-      float v[8];
+    // sixteen partials in flight (slabs past the last repeat it, unused), added in ascending order:
+    // one memory latency per sixteen, not per one
+    for (int k = 0; k < n_slab; k += 16) {
+      float v[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = pm[(int64_t)(k + u) * len + j];
+      for (int u = 0; u < 16; ++u) {
+        const int ks = k + u < n_slab ? k + u : n_slab - 1;
+        v[u] = pm[(int64_t)ks * stride + j];
+      }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) s += v[u];
+      for (int u = 0; u < 16; ++u)
+        if (k + u < n_slab) s += v[u];
     }
-    for (; k < n_slab; ++k) s += pm[(int64_t)k * len + j];
     const float gv = fmaf(s, scale, reg * theta_seg[j]);
     G[(int64_t)m * p_stride + j] = gv;
     mx = __float_as_uint(gv - Hq[(int64_t)m * p_stride + j]) & 0x7fffffffu;
@@ -676,6 +674,7 @@ struct MlpPlan {
   int64_t dz_off[LAQ_MAX_LAYERS];    // gradients w.r.t. pre-activations of hidden layer l
   int64_t dzc_off;                   // [S][C]
   int64_t part_off;                  // slab partial sums
+  int64_t part_len;                  // floats per (worker, slab)
   int32_t n_slab, rows_per_slab;
   int64_t rprod_off;                 // [M][rprod_count] block maxima of |g - h|
   int32_t rprod_count;
@@ -694,7 +693,7 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   }
   pl.dzc_off = off; off += align_up(pl.S * n.dims[n.n_layers], 64);
   // slabs of rows for the bandwidth-bound reductions (class-layer weights, biases)
-  int64_t want = ((int64_t)ctx->n_cu * 2 + ctx->M - 1) / ctx->M;
+  int64_t want = ((int64_t)ctx->n_cu * 6 + ctx->M - 1) / ctx->M;
   if (want < 1) want = 1;
   int64_t rps = (N_m + want - 1) / want;
   if (rps < 32) rps = 32;
@@ -703,8 +702,11 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   pl.n_slab = (int32_t)((N_m + rps - 1) / rps);
   int64_t widest = 0;
   for (int l = 1; l <= n.n_layers; ++l) widest = widest > n.dims[l] ? widest : n.dims[l];
-  const int64_t last_w = (int64_t)n.dims[n.n_layers - 1] * n.dims[n.n_layers];
-  const int64_t part_len = last_w > widest ? last_w : widest;
+  // class_grads_kernel leaves (b_{L-1} |) W_L | b_L partials side by side
+  const int64_t Kc = n.dims[n.n_layers - 1], Cc = n.dims[n.n_layers];
+  const int64_t class_len = (n.n_layers >= 2 ? Kc : 0) + Kc * Cc + Cc;
+  const int64_t part_len = class_len > widest ? class_len : widest;
+  pl.part_len = part_len;
   pl.part_off = off; off += align_up((int64_t)ctx->M * pl.n_slab * part_len, 64);
   // one radius slot per block of every kernel that writes a segment of G
   int64_t cnt = 0, splitk = 0;
@@ -721,8 +723,8 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
         cnt += ((out + t.bn - 1) / t.bn) * ((in + t.bm - 1) / t.bm);
       }
     }
-    else cnt += (in * out + kThreads - 1) / kThreads;                              // class layer
-    cnt += (out + kThreads - 1) / kThreads;                                         // bias
+    else cnt += (class_len + kThreads - 1) / kThreads;     // class layer, its bias, the last hidden layer's bias
+    if (l < n.n_layers - 1) cnt += (out + kThreads - 1) / kThreads;                 // bias of an earlier hidden layer
   }
   pl.rprod_count = (int32_t)cnt;
   pl.rprod_off = off; off += align_up((int64_t)ctx->M * cnt, 64);
@@ -820,26 +822,26 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   const int32_t rstride = pl.rprod_count;
   int32_t rbase = 0;
   ctx->rprod = rprod; ctx->rprod_stride = rstride; ctx->rprod_count = pl.rprod_count;
-  // ---- class layer gradients
+  // ---- class layer gradients, the residuals of the last hidden layer and its bias gradient
   {
     const int K = n.dims[L - 1];
+    const int has_prev = L >= 2 ? 1 : 0;
+    if (has_prev && n.offB[L - 2] + K != n.offW[L - 1])
+      return set_error(ctx, LAQ_EDEVICE, "internal: parameter layout is not (W_1, b_1, W_2, b_2, ...)");
+    if (n.offW[L - 1] + (int64_t)K * C != n.offB[L - 1])
+      return set_error(ctx, LAQ_EDEVICE, "internal: parameter layout is not (W_1, b_1, W_2, b_2, ...)");
+    const int64_t len = (has_prev ? K : 0) + (int64_t)K * C + C;
+    const int64_t seg = has_prev ? n.offB[L - 2] : n.offW[L - 1];
+    float* dZprev = has_prev ? ws + pl.dz_off[L - 1] : nullptr;
     const dim3 wg((unsigned)((K + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
-    hipLaunchKernelGGL(class_wgrad_kernel, wg, dim3(kThreads), 0, ctx->stream, Ain, ld_in, dZc, N_m, K, C,
-                       pl.rows_per_slab, part);
-    const int64_t len = (int64_t)K * C;
+    hipLaunchKernelGGL(class_grads_kernel, wg, dim3(kThreads), 0, ctx->stream, Ain, ld_in, dZc,
+                       theta + n.offW[L - 1], N_m, K, C, pl.rows_per_slab, has_prev, dZprev, (int64_t)K, part,
+                       pl.part_len);
     const unsigned wblocks = (unsigned)((len + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(slab_finish_kernel, dim3(wblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, part,
-                       pl.n_slab, len, theta + n.offW[L - 1], inv_N, reg, G + n.offW[L - 1],
-                       ctx->H + n.offW[L - 1], ctx->p_stride, rprod, rstride, rbase);
+                       pl.n_slab, len, pl.part_len, theta + seg, inv_N, reg, G + seg, ctx->H + seg, ctx->p_stride,
+                       rprod, rstride, rbase);
     rbase += (int32_t)wblocks;
-    const dim3 cg((unsigned)((C + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
-    hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZc, (int64_t)C, N_m, C,
-                       pl.rows_per_slab, part);
-    const unsigned bblocks = (unsigned)((C + kThreads - 1) / kThreads);
-    hipLaunchKernelGGL(slab_finish_kernel, dim3(bblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, part,
-                       pl.n_slab, (int64_t)C, theta + n.offB[L - 1], inv_N, reg, G + n.offB[L - 1],
-                       ctx->H + n.offB[L - 1], ctx->p_stride, rprod, rstride, rbase);
-    rbase += (int32_t)bblocks;
   }
   // ---- backward through the hidden layers
   const float* dZnext = dZc;     // gradient w.r.t. pre-activations of layer l+1
@@ -847,13 +849,7 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     float* dZl = ws + pl.dz_off[l];
     const float* Al = ws + pl.act_off[l];
     const int width = n.dims[l];
-    if (l == L - 1) {
-      int64_t runs = (S + 63) / 64;                       // runs of 64 rows
-      if (runs > 8192) runs = 8192;
-      const dim3 bg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)runs);
-      hipLaunchKernelGGL(class_backward_kernel, bg, dim3(kThreads), 0, ctx->stream, dZnext,
-                         theta + n.offW[L - 1], Al, (int64_t)width, S, width, C, dZl, (int64_t)width);
-    } else {
+    if (l < L - 1) {            // (the class layer's kernel has already left dZ_{L-1})
       // dZ_l = (dZ_{l+1} W_{l+1}^T) .* (A_l > 0)
       GemmArgs g{};
       g.A = dZnext; g.lda = n.dims[l + 1];
@@ -888,7 +884,7 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
         launch_gemm<true, false, EPI_PARTIAL>(ctx, g, ctx->M * ns, true);
         const unsigned wblocks = (unsigned)((len + kThreads - 1) / kThreads);
         hipLaunchKernelGGL(slab_finish_kernel, dim3(wblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, sp,
-                           ns, len, theta + n.offW[l - 1], inv_N, reg, G + n.offW[l - 1],
+                           ns, len, len, theta + n.offW[l - 1], inv_N, reg, G + n.offW[l - 1],
                            ctx->H + n.offW[l - 1], ctx->p_stride, rprod, rstride, rbase);
         rbase += (int32_t)wblocks;
       } else {
@@ -897,14 +893,15 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
         rbase += ((g.N + t.bn - 1) / t.bn) * ((g.M + t.bm - 1) / t.bm);
       }
     }
-    // db_l(m) = column sums of dZ_l(m)
-    {
+    // db_l(m) = column sums of dZ_l(m)   (l = L-1: done with the class layer)
+    if (l < L - 1) {
       const dim3 cg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
       hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZl, (int64_t)width, N_m, width,
                          pl.rows_per_slab, part);
       const unsigned bblocks = (unsigned)((width + kThreads - 1) / kThreads);
       hipLaunchKernelGGL(slab_finish_kernel, dim3(bblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
-                         part, pl.n_slab, (int64_t)width, theta + n.offB[l - 1], inv_N, reg, G + n.offB[l - 1],
+                         part, pl.n_slab, (int64_t)width, (int64_t)width, theta + n.offB[l - 1], inv_N, reg,
+                         G + n.offB[l - 1],
                          ctx->H + n.offB[l - 1], ctx->p_stride, rprod, rstride, rbase);
       rbase += (int32_t)bblocks;
     }

@@ -42,25 +42,57 @@ static int32_t ceil_log2(int64_t n) {
 
 __device__ __forceinline__ uint32_t abs_bits(float d) { return __float_as_uint(d) & 0x7fffffffu; }
 
+// Wavefront reductions; every lane gets the result.  Within each row of 16 lanes the values move
+// through the data-parallel-primitive path (row_shr 1, 2, 4, 8; lanes without a source read 0), which
+// costs an ordinary vector instruction per step; the four row totals (lanes 15, 31, 47, 63) are read
+// into scalar registers and combined there.  A butterfly of cross-lane shuffles through LDS takes
+// ~100 cycles per dependent step instead, which the small launches (one block per worker) feel.
+template <int CTRL>
+__device__ __forceinline__ uint32_t row_shr_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+__device__ __forceinline__ uint32_t lane_u32(uint32_t v, int lane) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    uint32_t o = (uint32_t)__shfl_xor((int)v, off);
-    v = v > o ? v : o;
-  }
-  return v;
+  uint32_t o;
+  o = row_shr_u32<0x111>(v); v = v > o ? v : o;
+  o = row_shr_u32<0x112>(v); v = v > o ? v : o;
+  o = row_shr_u32<0x114>(v); v = v > o ? v : o;
+  o = row_shr_u32<0x118>(v); v = v > o ? v : o;
+  const uint32_t a = lane_u32(v, 15), b = lane_u32(v, 31), c = lane_u32(v, 47), d = lane_u32(v, 63);
+  const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+  return ab > cd ? ab : cd;
+}
+
+template <int CTRL>
+__device__ __forceinline__ unsigned long long row_shr_u64(unsigned long long v) {
+  const uint32_t lo = row_shr_u32<CTRL>((uint32_t)v), hi = row_shr_u32<CTRL>((uint32_t)(v >> 32));
+  return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long lane_u64(unsigned long long v, int lane) {
+  return ((unsigned long long)lane_u32((uint32_t)(v >> 32), lane) << 32) | lane_u32((uint32_t)v, lane);
 }
 
 __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += (unsigned long long)__shfl_xor((long long)v, off);
-  return v;
+  v += row_shr_u64<0x111>(v);
+  v += row_shr_u64<0x112>(v);
+  v += row_shr_u64<0x114>(v);
+  v += row_shr_u64<0x118>(v);
+  return (lane_u64(v, 15) + lane_u64(v, 31)) + (lane_u64(v, 47) + lane_u64(v, 63));
 }
 
+// (fixed order: within a row lane 15 ends with ((x15 + x14) + (x13 + x12)) + ... , then the rows)
 __device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-  return v;
+  v += __longlong_as_double((long long)row_shr_u64<0x111>((unsigned long long)__double_as_longlong(v)));
+  v += __longlong_as_double((long long)row_shr_u64<0x112>((unsigned long long)__double_as_longlong(v)));
+  v += __longlong_as_double((long long)row_shr_u64<0x114>((unsigned long long)__double_as_longlong(v)));
+  v += __longlong_as_double((long long)row_shr_u64<0x118>((unsigned long long)__double_as_longlong(v)));
+  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+  const double r0 = __longlong_as_double((long long)lane_u64(b, 15)), r1 = __longlong_as_double((long long)lane_u64(b, 31));
+  const double r2 = __longlong_as_double((long long)lane_u64(b, 47)), r3 = __longlong_as_double((long long)lane_u64(b, 63));
+  return (r0 + r1) + (r2 + r3);
 }
 
 // Per-worker quantizer constants derived from the radius (eq. 5 denominators).
@@ -206,10 +238,16 @@ __device__ __forceinline__ void apply_skip_rule(const QuantArgs& a, int m, float
   // hterm[d] = xi_d * ||theta^{k+1-d} - theta^{k-d}||^2, fetched by D threads at once (a loop of
   // dependent global loads on one thread would cost a memory latency per term)
   double Hsum = 0.0;
-  for (int d = 0; d < a.D; ++d) {
-    const double term = d < kMaxHistLds ? hterm[d] : a.sc.xi[d] * a.sc.dtheta2[d];
-    Hsum = (d == 0) ? term : Hsum + term;
+  const int d_lds = a.D < kMaxHistLds ? a.D : kMaxHistLds;
+  for (int d0 = 0; d0 < d_lds; d0 += 8) {          // eight reads in flight, added in ascending order
+    double term[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) term[u] = hterm[d0 + u < d_lds ? d0 + u : d_lds - 1];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (d0 + u < d_lds) Hsum = (d0 + u == 0) ? term[u] : Hsum + term[u];
   }
+  for (int d = kMaxHistLds; d < a.D; ++d) Hsum = Hsum + a.sc.xi[d] * a.sc.dtheta2[d];
   const double a2 = (double)a.alpha * (double)a.alpha;
   const double m2 = (double)a.M * (double)a.M;
   const double cc = 1.0 / (a2 * m2);
@@ -250,7 +288,10 @@ __device__ __forceinline__ uint32_t quant_one(float g, float h, const QuantConst
   const double nd = (double)rintf(ldexpf(e, sh));   // integer-valued, |nd| < 2^21
   accN = fma(nd, nd, accN);                          // exact while accN < 2^53
   const int cc = 2 * (int)qi - L;                    // |cc| < 2^16
-  accS += (unsigned long long)(uint32_t)__mul24(cc, cc);
+  // unsigned: cc^2 reaches 2^32 - 2^17 at b = 16, past the range of the signed 24-bit product
+  // (whose overflow is undefined: the compiler then adds two squares in 32 bits and drops the carry)
+  const uint32_t ac = (uint32_t)(cc < 0 ? -cc : cc);
+  accS += (unsigned long long)(uint32_t)__umul24(ac, ac);   // (the header declares its result as int)
   return qi;
 }
 
@@ -307,27 +348,61 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     uint32_t rbits;
     if (a.rcount > 0) {
       const int lane = threadIdx.x & 63;
-      rbits = lane < a.rcount ? a.rsrc[(int64_t)m * a.rstride + lane] : 0u;
-      rbits = wave_max_u32(rbits);
+      rbits = a.rsrc[(int64_t)m * a.rstride + (lane < a.rcount ? lane : 0)];   // (duplicates do not change a maximum)
     } else {
       rbits = a.sc.Rfin[m];
     }
+    // One block per worker (small models): it applies the skip rule itself, and the call is a chain
+    // of memory latencies, not bandwidth.  Everything the block will read is requested here, before
+    // the first wait: up to four groups of g and h per thread, the terms of the skip rule.  The
+    // loads are unconditional, from clamped addresses, and their values are not touched until used.
+    const bool solo = a.fused_decide && gridDim.x == 1;
+    const bool quick = solo && a.U <= 4 && nfull >= 1;
+    __shared__ double hterm_s[kMaxHistLds];
+    const int dcl = (int)threadIdx.x < a.D ? (int)threadIdx.x : 0;
+    const double hx = a.sc.xi[dcl], hd = a.sc.dtheta2[dcl];
+    const double ehat2 = a.sc.Ehat2[m];
+    const int t_m = a.sc.t[m];
+    float4 qg[4][2], qh[4][2];
+    float tg[kGroup - 1], th[kGroup - 1];          // the p % 8 coordinates after the last whole group
+    if (quick) {
+#pragma unroll
+      for (int k = 0; k < kGroup - 1; ++k) {
+        const int64_t i = nfull * kGroup + k < a.p ? nfull * kGroup + k : a.p - 1;
+        tg[k] = g[i]; th[k] = h[i];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int64_t grp = first + (int64_t)u * kThreads;
+        grp = grp < nfull ? grp : nfull - 1;
+        const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
+        const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
+        qg[u][0] = gp[0]; qg[u][1] = gp[1]; qh[u][0] = hp[0]; qh[u][1] = hp[1];
+      }
+    }
+    if (a.rcount > 0) rbits = wave_max_u32(rbits);
     const QuantConst c = quant_const<B>(rbits);
     const int sh = a.eps_K - c.x;
     double accN = 0.0;
     unsigned long long accS = 0;
-    // one block per worker: it applies the skip rule itself; what the rule needs is fetched now,
-    // long before it is used
-    const bool solo = a.fused_decide && gridDim.x == 1;
-    __shared__ double hterm_s[kMaxHistLds];
-    double ehat2 = 0.0;
-    int t_m = 0;
-    if (solo) {
-      stage_history(a, hterm_s);
-      if (threadIdx.x == 0) { ehat2 = a.sc.Ehat2[m]; t_m = a.sc.t[m]; }
-    }
 
-    if (c.zero) {
+    if (quick) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t grp = first + (int64_t)u * kThreads;
+        if (u < a.U && grp < nfull) {
+          unsigned __int128 v = 0;
+          if (!c.zero) {
+            const float gv[8] = {qg[u][0].x, qg[u][0].y, qg[u][0].z, qg[u][0].w, qg[u][1].x, qg[u][1].y, qg[u][1].z, qg[u][1].w};
+            const float hv[8] = {qh[u][0].x, qh[u][0].y, qh[u][0].z, qh[u][0].w, qh[u][1].x, qh[u][1].y, qh[u][1].z, qh[u][1].w};
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j)
+              v |= (unsigned __int128)quant_one<B>(gv[j], hv[j], c, sh, accN, accS) << (j * B);
+          }
+          store_group<B>(out + grp * B, v);
+        }
+      }
+    } else if (c.zero) {
       for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads)
         store_group<B>(out + grp * B, 0);
     } else {
@@ -344,15 +419,24 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
         store_group<B>(out + grp * B, v);
       }
     }
+    if (solo && (int)threadIdx.x < a.D && (int)threadIdx.x < kMaxHistLds) hterm_s[threadIdx.x] = hx * hd;
     // ragged tail (p % 8 coordinates) and zero fill up to the row stride
     if (blockIdx.x == 0 && threadIdx.x == 0) {
       int64_t byte = nfull * B;
       if (a.p > nfull * kGroup) {
         unsigned __int128 v = 0;
-        if (!c.zero)
-          for (int64_t i = nfull * kGroup; i < a.p; ++i)
-            v |= (unsigned __int128)quant_one<B>(g[i], h[i], c, sh, accN, accS)
-                 << ((int)(i - nfull * kGroup) * B);
+        if (!c.zero) {
+          if (quick) {
+#pragma unroll
+            for (int k = 0; k < kGroup - 1; ++k)
+              if (nfull * kGroup + k < a.p)
+                v |= (unsigned __int128)quant_one<B>(tg[k], th[k], c, sh, accN, accS) << (k * B);
+          } else {
+            for (int64_t i = nfull * kGroup; i < a.p; ++i)
+              v |= (unsigned __int128)quant_one<B>(g[i], h[i], c, sh, accN, accS)
+                   << ((int)(i - nfull * kGroup) * B);
+          }
+        }
         for (int k = 0; k < B; ++k) out[byte + k] = (uint8_t)(v >> (8 * k));
         byte += B;
       }
@@ -548,18 +632,22 @@ struct FinishFetch {
 
 // own_total: the sum of ||nabla||^2 when the calling block is the whole grid (then no partial is read)
 __device__ __forceinline__ FinishFetch finish_fetch(const ServerArgs& a, int n_blocks, bool own_total) {
+  // Every load is unconditional, from an index clamped into its array, and nothing here looks at a
+  // loaded value: a load under a branch, or one whose value is used at once, makes the thread wait
+  // for it on the spot, and the block would pay one memory latency per array again.
   FinishFetch f;
   const int m = threadIdx.x;
-  const bool have = m < a.M;
-  f.up = have ? a.upload[m] : (uint8_t)0;
-  f.e2 = have ? a.sc.E2[m] : 0.0;
-  f.t = have ? a.sc.t[m] : 0;
-  f.n_uploads = have ? a.sc.uploads[m] : 0ull;
-  f.part = (!own_total && m < n_blocks)
-               ? __hip_atomic_load(&a.sc.srv_part[m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-               : 0.0;
+  const int mc = m < a.M ? m : a.M - 1;
+  f.up = a.upload[mc];
+  f.e2 = a.sc.E2[mc];
+  f.t = a.sc.t[mc];
+  f.n_uploads = a.sc.uploads[mc];
+  f.part = 0.0;
+  if (!own_total)
+    f.part = __hip_atomic_load(&a.sc.srv_part[m < n_blocks ? m : n_blocks - 1], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
   const int d = a.D - 1 - m;
-  f.older = d >= 1 ? a.sc.dtheta2[d - 1] : 0.0;
+  f.older = a.sc.dtheta2[d >= 1 ? d - 1 : 0];
   return f;
 }
 
@@ -591,9 +679,15 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   const int64_t span = (int64_t)gridDim.x * kThreads;
   const int64_t grp0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   float4 pn[kServerJ][2], pt[kServerJ][2];
+  float tn[kGroup - 1], tt[kGroup - 1];            // the p % 8 coordinates after the last whole group
   FinishFetch ff;
   if constexpr (SOLO) {
     ff = finish_fetch(a, 1, true);
+#pragma unroll
+    for (int k = 0; k < kGroup - 1; ++k) {
+      const int64_t i = nfull * kGroup + k < a.p ? nfull * kGroup + k : a.p - 1;
+      tn[k] = a.nabla[i]; tt[k] = a.theta[i];
+    }
 #pragma unroll
     for (int j = 0; j < kServerJ; ++j) {
       const int64_t grp = grp0 + j * span;
@@ -727,10 +821,18 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
         }
         acc1 = acc1 + dq;
       }
-      const float nb = a.nabla[i] + acc1;
+      float nb_old = 0.0f, th_old = 0.0f;
+      if constexpr (SOLO) {                          // fetched at the start of the kernel
+#pragma unroll
+        for (int k = 0; k < kGroup - 1; ++k)
+          if (i == nfull * kGroup + k) { nb_old = tn[k]; th_old = tt[k]; }
+      } else {
+        nb_old = a.nabla[i]; th_old = a.theta[i];
+      }
+      const float nb = nb_old + acc1;
       a.nabla[i] = nb;
       const float st = a.alpha * nb;
-      a.theta[i] = a.theta[i] - st;
+      a.theta[i] = th_old - st;
       n2 = fma((double)nb, (double)nb, n2);
     }
   }
@@ -797,7 +899,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
   if (own_total) {
     tot = threadIdx.x == 0 ? *own_total : 0.0;
   } else {
-    tot = f.part;
+    tot = (int)threadIdx.x < n_blocks ? f.part : 0.0;
     for (int i = threadIdx.x + kThreads; i < n_blocks; i += kThreads)
       tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -813,7 +915,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
   for (int base = a.D - 1; base >= 0; base -= kThreads) {        // highest chunk first
     const int d = base - (int)threadIdx.x;                       // this thread's destination
     double v = 0.0;
-    if (first) v = f.older;                                      // fetched before anything was written
+    if (first) v = f.older;                                      // fetched before anything was written (used if d >= 1)
     else if (d >= 1) v = a.sc.dtheta2[d - 1];
     first = false;
     __syncthreads();

@@ -417,8 +417,15 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
   if (i < p) {
     const float* pm = part + (int64_t)m * n_blk * p;
     float s = 0.0f;
-#pragma unroll 8
-    for (int k = 0; k < n_blk; ++k) s += pm[(int64_t)k * p + i];
+    // sixteen block partials in flight (blocks past the last repeat it, unused), added in ascending order
+    for (int k = 0; k < n_blk; k += 16) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = pm[(int64_t)(k + u < n_blk ? k + u : n_blk - 1) * p + i];
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (k + u < n_blk) s += v[u];
+    }
     const float g = fmaf(s, inv_N, reg * theta[i]);
     G[(int64_t)m * p_stride + i] = g;
     mx = __float_as_uint(g - H[(int64_t)m * p_stride + i]) & 0x7fffffffu;

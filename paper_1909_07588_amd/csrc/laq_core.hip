@@ -336,7 +336,10 @@ __device__ __forceinline__ unsigned __int128 load_group(const uint8_t* in) {
   }
 }
 
-template <int B>
+// SOLO: one block per worker (small models; the launch is a chain of memory latencies, not
+// bandwidth).  The block applies the skip rule itself and requests everything it will read before
+// its first wait.  The streaming instantiation stays lean: it lives on occupancy.
+template <int B, bool SOLO>
 __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
   const int64_t nfull = a.p / kGroup;
   const int64_t first = (int64_t)blockIdx.x * a.U * kThreads + threadIdx.x;
@@ -352,17 +355,20 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     } else {
       rbits = a.sc.Rfin[m];
     }
-    // One block per worker (small models): it applies the skip rule itself, and the call is a chain
-    // of memory latencies, not bandwidth.  Everything the block will read is requested here, before
-    // the first wait: up to four groups of g and h per thread, the terms of the skip rule.  The
-    // loads are unconditional, from clamped addresses, and their values are not touched until used.
-    const bool solo = a.fused_decide && gridDim.x == 1;
-    const bool quick = solo && a.U <= 4 && nfull >= 1;
-    __shared__ double hterm_s[kMaxHistLds];
-    const int dcl = (int)threadIdx.x < a.D ? (int)threadIdx.x : 0;
-    const double hx = a.sc.xi[dcl], hd = a.sc.dtheta2[dcl];
-    const double ehat2 = a.sc.Ehat2[m];
-    const int t_m = a.sc.t[m];
+    // SOLO: everything the block will read is requested here, before the first wait: up to four
+    // groups of g and h per thread, the ragged tail, the terms of the skip rule.  The loads are
+    // unconditional, from clamped addresses, and their values are not touched until used.
+    constexpr bool solo = SOLO;
+    const bool quick = SOLO && a.U <= 4 && nfull >= 1;
+    __shared__ double hterm_s[SOLO ? kMaxHistLds : 1];
+    double hx = 0.0, hd = 0.0, ehat2 = 0.0;
+    int t_m = 0;
+    if constexpr (SOLO) {
+      const int dcl = (int)threadIdx.x < a.D ? (int)threadIdx.x : 0;
+      hx = a.sc.xi[dcl]; hd = a.sc.dtheta2[dcl];
+      ehat2 = a.sc.Ehat2[m];
+      t_m = a.sc.t[m];
+    }
     float4 qg[4][2], qh[4][2];
     float tg[kGroup - 1], th[kGroup - 1];          // the p % 8 coordinates after the last whole group
     if (quick) {
@@ -1021,7 +1027,11 @@ static bool valid_sizes(int32_t M, int64_t p, int32_t b, int32_t D) {
 
 template <int B>
 static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
-  hipLaunchKernelGGL(codes_kernel<B>, grid, dim3(kThreads), 0, s, a);
+  if (grid.x == 1 && a.fused_decide) {
+    hipLaunchKernelGGL((codes_kernel<B, true>), grid, dim3(kThreads), 0, s, a);
+    return;
+  }
+  hipLaunchKernelGGL((codes_kernel<B, false>), grid, dim3(kThreads), 0, s, a);
   if (!a.fused_decide)
     hipLaunchKernelGGL(decide_kernel<B>, dim3((unsigned)a.M), dim3(kThreads), 0, s, a, (int32_t)grid.x);
 }

@@ -143,8 +143,10 @@ def model_rooflines(w, ph, traffic):
     return out
 
 
-def run_stress(b, steps, warmup):
-    """Quantize/skip/aggregate bandwidth stress (synthetic gradients, no model)."""
+def run_stress(b, steps, warmup, handover=False):
+    """Quantize/skip/aggregate bandwidth stress (synthetic gradients, no model).
+    handover: the untimed generator of the gradients also leaves max |g - h| per worker, as a
+    gradient kernel's epilogue would (laq_radius_handover); laq_quantize_skip is then one pass."""
     import torch
     import laq_synth
     import paper_1909_07588_amd as laq
@@ -159,7 +161,14 @@ def run_stress(b, steps, warmup):
     tq = ts = 0.0
     n_up = 0
     ups = []
+    H = ctx.state()["H"] if handover else None
+    rmax = torch.zeros((M, 1), dtype=torch.float32, device=dev)
     for it in range(warmup + steps):
+        if handover:                                   # part of producing the gradients: not timed
+            for m in range(M):
+                torch.sub(G[m], H[m], out=tmp)
+                rmax[m, 0] = tmp.abs_().max()
+            ctx.laq_radius_handover(G, rmax.view(torch.int32))
         ev = _events(torch, 3)
         ev[0].record()
         ctx.laq_quantize_skip(G, codes, R, up)
@@ -180,7 +189,8 @@ def run_stress(b, steps, warmup):
     alg_q = elems * (8 + b / 8) / 1e9
     alg_s = (n_up / steps) * p * (8 + b / 8) / 1e9 + 16 * p / 1e9
     res = {
-        "workload": f"{w.name}_b{b}", "M": M, "p": p, "b": b, "steps": steps,
+        "workload": f"{w.name}_b{b}" + ("_radius_handover" if handover else ""), "M": M, "p": p, "b": b,
+        "steps": steps,
         "iterations_per_s": round(1e3 / (tq + ts), 2), "ms_per_step": round(tq + ts, 4),
         "phase_ms": {"quantize_skip": round(tq, 4), "server_step": round(ts, 4)},
         "upload_fraction": round(n_up / (steps * M), 4),
@@ -349,6 +359,16 @@ def main():
             }
             workloads.append(r)
             torch.cuda.empty_cache()
+        # the same stress with the radius handed over by the (untimed) producer of the gradients
+        r, (alg_q, tq, alg_s, ts) = run_stress(4, 30, 3, handover=True)
+        r["rooflines"] = {
+            "quantize_skip": _roofline("hbm", alg_q / (tq * 1e-3), HBM_PEAK_GBS, "GB/s", None, "codes_kernel",
+                                       "single pass: max |g - h| per worker comes with the gradients "
+                                       "(laq_radius_handover), as from laq_worker_grads' epilogues"),
+            "server_step": _roofline("hbm", alg_s / (ts * 1e-3), HBM_PEAK_GBS, "GB/s", None, "server_kernel"),
+        }
+        workloads.append(r)
+        torch.cuda.empty_cache()
 
     line = {
         "metric": "LAQ iterations/sec and worker-gradient GB/s quantized (fraction of HBM peak)",

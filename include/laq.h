@@ -185,6 +185,22 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev,
                       float* R_dev, uint8_t* upload_dev);
 
 /*
+ * For a caller whose own kernel produces the gradients (Sec. 2.1 defines R_m
+ * from g_m and the stored Q_m alone, so whoever writes g_m can take the
+ * maximum on the way, as laq_worker_grads does): declares that
+ * rmax_dev[m * count + i], i < count, hold the raw bits of max |g_j - h_j| over
+ * the i-th part of any partition of worker m's coordinates (h = the stored
+ * quantized gradients, laq_state_view.H_dev).  The next laq_quantize_skip on
+ * the same G_dev then skips its radius pass, provided the state has not
+ * changed in between (laq_server_step, laq_set_state, laq_get_state and
+ * laq_reset withdraw the declaration).  rmax_dev (device, caller-owned) is read
+ * when laq_quantize_skip runs.  The values are trusted: if their maximum is
+ * not ||g_m - h_m||_inf the codes are those of eq. 5 for that other radius,
+ * clamped to [0, L].  count >= 1.
+ */
+int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_dev, int32_t count);
+
+/*
  * Server update (eq. 4) and the bookkeeping of Algorithm 2: for workers with
  * upload_dev[m] = 1, in ascending m: delta from (R_m, q_m), stored
  * Q_m += delta, acc_i += delta_i, ||eps_hat_m||^2 = ||eps_m||^2, t_m = 0,

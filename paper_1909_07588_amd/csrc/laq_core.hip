@@ -1250,6 +1250,22 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   return LAQ_OK;
 }
 
+int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_dev, int32_t count) {
+  if (!ctx) return LAQ_EINVAL;
+  if (!G_dev || !rmax_dev || count < 1)
+    return set_error(ctx, LAQ_EINVAL, "laq_radius_handover: null pointer or count < 1");
+  ctx->rprod = const_cast<uint32_t*>(rmax_dev);
+  ctx->rprod_stride = count;
+  ctx->rprod_count = count;
+  if (count > 64) {
+    hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, ctx->rprod,
+                       count, count, ctx->sc.Rfin);
+    LAQ_HIP(ctx, hipGetLastError());
+  }
+  ctx->radius_for = G_dev;
+  return LAQ_OK;
+}
+
 int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
                     const uint8_t* upload_dev, float* theta_dev) {
   if (!ctx) return LAQ_EINVAL;

@@ -363,6 +363,43 @@ def test_largest_network_widths_at_reduced_batch():
     assert err.max() <= 1e-5, err
 
 
+@pytest.mark.parametrize("M,p,b,count", [(5, 300_007, 4, 37), (3, 4100, 3, 1), (4, 70_001, 8, 200), (10, 7850, 3, 64)])
+def test_radius_handed_over_by_the_caller(M, p, b, count):
+    """A caller's own producer of gradients leaves block maxima of |g - h| (here: torch ops on the
+    library's stored gradients, over an uneven partition of the coordinates); laq_quantize_skip then
+    runs without its radius pass and must still give the oracle's codes, radii and decisions."""
+    rng = np.random.default_rng(M * 31 + p)
+    ctx, st, theta = make_pair(M, p, b, D=5, t_bar=8, alpha=0.02)
+    _random_state(st, rng)
+    push_state(ctx, st)
+    theta.copy_(torch.from_numpy(st.theta))
+    G = (st.H + rng.standard_normal((M, p)).astype(np.float32)
+         * (10.0 ** rng.uniform(-4, 0, (M, 1))).astype(np.float32)).astype(np.float32)
+    Gd = to_dev_G(ctx, G)
+    Hd = ctx.state()["H"]
+    cuts = np.unique(np.concatenate([[0, p], rng.integers(0, p + 1, count - 1)]))
+    while len(cuts) < count + 1:                       # empty parts are fine: their maximum is 0
+        cuts = np.sort(np.concatenate([cuts, [p]]))
+    d = (Gd[:, :p] - Hd[:, :p]).abs()
+    rmax = torch.zeros((M, count), dtype=torch.float32, device=DEV)
+    for i in range(count):
+        lo, hi = int(cuts[i]), int(cuts[i + 1])
+        if hi > lo:
+            rmax[:, i] = d[:, lo:hi].amax(dim=1)
+    rbits = rmax.view(torch.int32).contiguous()
+    ctx.laq_radius_handover(Gd, rbits)
+    msgs, _ = check_quantize(ctx, st, Gd, G)
+    # the declaration survives a repeated call, and is withdrawn by the server step
+    ctx.laq_radius_handover(Gd, rbits)
+    msgs, _ = check_quantize(ctx, st, Gd, G, msgs)
+    check_server(ctx, st, theta, msgs, G)
+    push_state(ctx, st)
+    rbits.zero_()                                      # stale values: must not be read any more
+    G2 = (st.H + 0.01 * rng.standard_normal((M, p))).astype(np.float32)
+    Gd[:, :p].copy_(torch.from_numpy(G2))
+    check_quantize(ctx, st, Gd, G2)
+
+
 def test_radius_handed_over_by_the_gradient_kernels_is_dropped_when_the_state_changes():
     """laq_worker_grads leaves the radius for laq_quantize_skip; overwriting the stored
     gradients through the state view in between must fall back to the radius pass."""

@@ -389,7 +389,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // quarter q = lane/16) streams A[i][16t + 4q .. +3] straight from HBM (each
 // activation is used once) while W^T sits in LDS as the B operand; the softmax
 // is a 16-lane butterfly on the accumulator layout.  No barrier in the loop.
-__global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __restrict__ Aact, int64_t lda,
+// The kernel lives on loads in flight: four chunks (64 bytes per lane) are requested before the
+// first is multiplied, and when W^T is so large that only one block fits a CU the block has
+// sixteen wavefronts instead of four.
+__global__ __launch_bounds__(1024) void class_forward_kernel(const float* __restrict__ Aact, int64_t lda,
                                                                  const float* __restrict__ W,
                                                                  const float* __restrict__ bias,
                                                                  const int32_t* __restrict__ y, int64_t S,
@@ -397,24 +400,43 @@ __global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __
                                                                  float* __restrict__ dZ) {
   extern __shared__ __attribute__((aligned(16))) float Wt[];   // [C][ldsK], columns >= K zero
   const int nchunk = (K + 15) / 16, KP = nchunk * 16;
-  for (int idx = threadIdx.x; idx < C * KP; idx += kThreads) {
-    const int c = idx / KP, k = idx - c * KP;
-    Wt[c * ldsK + k] = k < K ? W[(int64_t)k * C + c] : 0.0f;
+  // W^T into LDS, eight loads in flight per thread (unconditional, from clamped indices)
+  for (int i0 = threadIdx.x; i0 < C * KP; i0 += 8 * (int)blockDim.x) {
+    float wv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = i0 + u * (int)blockDim.x;
+      const int c = idx / KP, k = idx - c * KP;
+      wv[u] = W[(c < C && k < K) ? (int64_t)k * C + c : 0];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = i0 + u * (int)blockDim.x;
+      const int c = idx / KP, k = idx - c * KP;
+      if (idx < C * KP) Wt[c * ldsK + k] = k < K ? wv[u] : 0.0f;
+    }
   }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
   const int64_t n_tiles = (S + 15) / 16;
-  const int64_t stride = (int64_t)gridDim.x * (kThreads / 64);
+  const int waves = (int)blockDim.x / 64;
+  const int64_t stride = (int64_t)gridDim.x * waves;
   const float bj = l16 < C ? bias[l16] : 0.0f;
-  for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < n_tiles; tile += stride) {
+  for (int64_t tile = (int64_t)blockIdx.x * waves + wave; tile < n_tiles; tile += stride) {
     const int64_t row0 = tile * 16;
     int64_t ra = row0 + l16;
     ra = ra < S ? ra : S - 1;
     const float* arow = Aact + ra * lda + 4 * lq;
     const float* wrow = Wt + l16 * ldsK + 4 * lq;
+    int ylab[4];                                      // labels of this lane's four rows, requested now
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t row = row0 + 4 * lq + r;
+      ylab[r] = y[row < S ? row : S - 1];
+    }
     floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-    auto chunk = [&](int t, floatx4& acc) {
+    auto fetch = [&](int t) {
       const int k = 16 * t + 4 * lq;
       float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
       if (vec && k + 3 < K) {
@@ -425,6 +447,9 @@ __global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __
         if (k + 2 < K) a.z = arow[16 * t + 2];
         if (k + 3 < K) a.w = arow[16 * t + 3];
       }
+      return a;
+    };
+    auto multiply = [&](int t, const float4& a, floatx4& acc) {
       float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
       if (l16 < C) b = *reinterpret_cast<const float4*>(wrow + 16 * t);
       acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc, 0, 0, 0);
@@ -432,13 +457,37 @@ __global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __
       acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc, 0, 0, 0);
     };
-    int t = 0;
-#pragma unroll 2
-    for (; t + 1 < nchunk; t += 2) {   // two independent accumulator chains
-      chunk(t, acc0);
-      chunk(t + 1, acc1);
+    if (vec && (K & 3) == 0) {
+      // aligned rows: eight unconditional loads in flight (chunks past the row repeat its last
+      // float4, unused), nothing looks at a value before its turn to be multiplied
+      for (int t0 = 0; t0 < nchunk; t0 += 8) {
+        float4 a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int k = 16 * (t0 + u) + 4 * lq;
+          a[u] = *reinterpret_cast<const float4*>(arow - 4 * lq + (k < K ? k : K - 4));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (t0 + u < nchunk) {                      // uniform
+            const int k = 16 * (t0 + u) + 4 * lq;
+            float4 v = a[u];
+            if (k >= K) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            multiply(t0 + u, v, (u & 1) ? acc1 : acc0);
+          }
+        }
+      }
+    } else {
+      int t = 0;
+      for (; t + 3 < nchunk; t += 4) {   // four loads in flight, two independent accumulator chains
+        const float4 a0 = fetch(t), a1 = fetch(t + 1), a2 = fetch(t + 2), a3 = fetch(t + 3);
+        multiply(t, a0, acc0);
+        multiply(t + 1, a1, acc1);
+        multiply(t + 2, a2, acc0);
+        multiply(t + 3, a3, acc1);
+      }
+      for (; t < nchunk; ++t) multiply(t, fetch(t), acc0);
     }
-    if (t < nchunk) chunk(t, acc0);
     // lane holds Z[4 lq + r][l16], r = 0..3
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -452,7 +501,7 @@ __global__ __launch_bounds__(kThreads) void class_forward_kernel(const float* __
       float den = e;
 #pragma unroll
       for (int off = 8; off > 0; off >>= 1) den += __shfl_xor(den, off);
-      if (valid && row < S) dZ[row * C + l16] = e / den - (l16 == y[row] ? 1.0f : 0.0f);
+      if (valid && row < S) dZ[row * C + l16] = e / den - (l16 == ylab[r] ? 1.0f : 0.0f);
     }
   }
 }
@@ -806,13 +855,15 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     if (smem > 160 * 1024)
       return set_error(ctx, LAQ_EINVAL, "MLP: last hidden width * classes does not fit LDS");
     const int64_t tiles = (S + 15) / 16;
-    int64_t blocks = (tiles + 3) / 4;
-    const int64_t cap = (int64_t)ctx->n_cu * 8;
+    const int cf_threads = smem > 40 * 1024 ? 1024 : kThreads;      // one block per CU: make it a large one
+    const int cf_waves = cf_threads / 64;
+    int64_t blocks = (tiles + cf_waves - 1) / cf_waves;
+    const int64_t cap = (int64_t)ctx->n_cu * (cf_threads == kThreads ? 8 : 1);
     if (blocks > cap) blocks = cap;
     if (smem > 48 * 1024)
       LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(class_forward_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL(class_forward_kernel, dim3((unsigned)blocks), dim3(kThreads), smem, ctx->stream, Ain,
+    hipLaunchKernelGGL(class_forward_kernel, dim3((unsigned)blocks), dim3((unsigned)cf_threads), smem, ctx->stream, Ain,
                        ld_in, theta + n.offW[L - 1], theta + n.offB[L - 1], ctx->y, S, K, C, ldsK,
                        vec_ok(Ain, ld_in), dZc);
   }

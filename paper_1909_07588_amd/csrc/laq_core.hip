@@ -793,41 +793,53 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
       tp4[1] = make_float4(tv[4], tv[5], tv[6], tv[7]);
     }
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  // The p % 8 coordinates after the last whole group: wavefront 0 of block 0.  Lane l takes the
+  // l-th uploader of a round of 64 (all their loads are in flight together; one thread walking the
+  // uploaders would pay two memory latencies for each), then the contributions are added in
+  // ascending worker order.
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    const int lane = threadIdx.x;
     for (int64_t i = nfull * kGroup; i < a.p; ++i) {
       float acc1 = 0.0f;
-      for (int k = 0; k < n_up; ++k) {
-        const int m = list[k];
-        const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
-        float* hp = a.H + (int64_t)m * a.p_stride + i;
-        float dq;
-        if constexpr (B == kExact) {
-          const float gval = reinterpret_cast<const float*>(row)[i];
-          dq = gval - *hp;
-          *hp = gval;
-        } else {
-          const int64_t bit = i * B;
-          uint32_t q = 0;
-          for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
-          dq = (float)q * stepm[m];
-          dq = dq - Rm[m];
-          *hp = *hp + dq;
+      for (int k0 = 0; k0 < n_up; k0 += 64) {
+        const int k = k0 + lane;
+        float dq = 0.0f;
+        if (k < n_up) {
+          const int m = list[k];
+          const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+          float* hp = a.H + (int64_t)m * a.p_stride + i;
+          if constexpr (B == kExact) {
+            const float gval = reinterpret_cast<const float*>(row)[i];
+            dq = gval - *hp;
+            *hp = gval;
+          } else {
+            const int64_t bit = i * B;
+            uint32_t q = 0;
+            for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
+            dq = (float)q * stepm[m];
+            dq = dq - Rm[m];
+            *hp = *hp + dq;
+          }
         }
-        acc1 = acc1 + dq;
+        const int cnt = n_up - k0 < 64 ? n_up - k0 : 64;
+        for (int l = 0; l < cnt; ++l)
+          acc1 = acc1 + __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dq), l));
       }
-      float nb_old = 0.0f, th_old = 0.0f;
-      if constexpr (SOLO) {                          // fetched at the start of the kernel
+      if (lane == 0) {
+        float nb_old = 0.0f, th_old = 0.0f;
+        if constexpr (SOLO) {                          // fetched at the start of the kernel
 #pragma unroll
-        for (int k = 0; k < kGroup - 1; ++k)
-          if (i == nfull * kGroup + k) { nb_old = tn[k]; th_old = tt[k]; }
-      } else {
-        nb_old = a.nabla[i]; th_old = a.theta[i];
+          for (int k = 0; k < kGroup - 1; ++k)
+            if (i == nfull * kGroup + k) { nb_old = tn[k]; th_old = tt[k]; }
+        } else {
+          nb_old = a.nabla[i]; th_old = a.theta[i];
+        }
+        const float nb = nb_old + acc1;
+        a.nabla[i] = nb;
+        const float st = a.alpha * nb;
+        a.theta[i] = th_old - st;
+        n2 = fma((double)nb, (double)nb, n2);
       }
-      const float nb = nb_old + acc1;
-      a.nabla[i] = nb;
-      const float st = a.alpha * nb;
-      a.theta[i] = th_old - st;
-      n2 = fma((double)nb, (double)nb, n2);
     }
   }
 

@@ -645,11 +645,12 @@ __device__ __forceinline__ FinishFetch finish_fetch(const ServerArgs& a, int n_b
   return f;
 }
 
-template <int B>
+template <int B, int NT>
 __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks, const FinishFetch& f,
                                               const double* own_total);
 
 constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
+constexpr int kSoloThreads = 1024;   // block size of the one-block launches (4 tiles of 256 groups at most)
 
 // eq. 4: nabla^k = nabla^{k-1} + sum_{m in M^k} deltaQ_m, theta^{k+1} = theta^k - alpha nabla^k,
 // with Q_m(theta_hat_m) += deltaQ_m for the uploading workers (Alg. 2, upload branch).
@@ -661,7 +662,9 @@ constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
 // at the start, so that a call on a small model pays for three dependent memory round trips
 // (upload flags, message rows, stores) instead of seven.
 template <int B, bool SOLO>
-__global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
+__global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void server_kernel(ServerArgs a) {
+  constexpr int NT = SOLO ? kSoloThreads : kThreads;   // SOLO: sixteen wavefronts, one group of 8 coordinates per lane
+  constexpr int JN = SOLO ? 1 : kServerJ;
   constexpr uint32_t L = B >= 32 ? 0xffffffffu : (1u << (B & 31)) - 1u;
   extern __shared__ unsigned char smem_raw[];
   int32_t* list = reinterpret_cast<int32_t*>(smem_raw);           // [M] uploading workers, ascending
@@ -670,9 +673,9 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   __shared__ int n_up_s;
 
   const int64_t nfull = a.p / kGroup;
-  const int64_t span = (int64_t)gridDim.x * kThreads;
-  const int64_t grp0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  float4 pn[kServerJ][2], pt[kServerJ][2];
+  const int64_t span = (int64_t)gridDim.x * NT;
+  const int64_t grp0 = (int64_t)blockIdx.x * NT + threadIdx.x;
+  float4 pn[JN][2], pt[JN][2];
   float tn[kGroup - 1], tt[kGroup - 1];            // the p % 8 coordinates after the last whole group
   FinishFetch ff;
   if constexpr (SOLO) {
@@ -683,7 +686,7 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
       tn[k] = a.nabla[i]; tt[k] = a.theta[i];
     }
 #pragma unroll
-    for (int j = 0; j < kServerJ; ++j) {
+    for (int j = 0; j < JN; ++j) {
       const int64_t grp = grp0 + j * span;
       if (j < a.J && grp < nfull) {
         const float4* np4 = reinterpret_cast<const float4*>(a.nabla + grp * kGroup);
@@ -695,9 +698,9 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
 
   // ascending list of workers whose message carries a non-zero innovation
   // (order-preserving compaction: wavefront ballots + prefix counts)
-  __shared__ int wave_cnt[kThreads / 64];
+  __shared__ int wave_cnt[NT / 64];
   if (threadIdx.x == 0) n_up_s = 0;
-  for (int base = 0; base < a.M; base += kThreads) {
+  for (int base = 0; base < a.M; base += NT) {
     const int m = base + threadIdx.x;
     bool on = false;
     if (m < a.M) {
@@ -715,14 +718,19 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
     for (int wv = 0; wv < wave; ++wv) before += wave_cnt[wv];
     if (on) list[before + __popcll(bal & ((1ull << lane) - 1ull))] = m;
     __syncthreads();
-    if (threadIdx.x == 0) n_up_s += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    if (threadIdx.x == 0) {
+      int tot = 0;
+#pragma unroll
+      for (int wv = 0; wv < NT / 64; ++wv) tot += wave_cnt[wv];
+      n_up_s += tot;
+    }
     __syncthreads();
   }
   const int n_up = n_up_s;
 
-  float acc[kServerJ][kGroup];
+  float acc[JN][kGroup];
 #pragma unroll
-  for (int j = 0; j < kServerJ; ++j)
+  for (int j = 0; j < JN; ++j)
 #pragma unroll
     for (int i = 0; i < kGroup; ++i) acc[j][i] = 0.0f;
   for (int k = 0; k < n_up; ++k) {
@@ -731,7 +739,7 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
     const uint8_t* crow = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
     float* hrow = a.H + (int64_t)m * a.p_stride;
 #pragma unroll
-    for (int j = 0; j < kServerJ; ++j) {
+    for (int j = 0; j < JN; ++j) {
       const int64_t grp = grp0 + j * span;
       if (j < a.J && grp < nfull) {
         float4* hp = reinterpret_cast<float4*>(hrow + grp * kGroup);
@@ -766,7 +774,7 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
 
   double n2 = 0.0;
 #pragma unroll
-  for (int j = 0; j < kServerJ; ++j) {
+  for (int j = 0; j < JN; ++j) {
     const int64_t grp = grp0 + j * span;
     if (j < a.J && grp < nfull) {
       float4* np4 = reinterpret_cast<float4*>(a.nabla + grp * kGroup);
@@ -844,15 +852,20 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
   }
 
   n2 = wave_sum_f64(n2);
-  __shared__ double smd[kThreads / 64];
+  __shared__ double smd[NT / 64];
   __shared__ bool last_s;
   if ((threadIdx.x & 63) == 0) smd[threadIdx.x >> 6] = n2;
   __syncthreads();
   if constexpr (SOLO) {
     __shared__ double total_s;
-    if (threadIdx.x == 0) total_s = (smd[0] + smd[1]) + (smd[2] + smd[3]);
+    if (threadIdx.x == 0) {
+      double tot = 0.0;
+#pragma unroll
+      for (int wv = 0; wv < NT / 64; ++wv) tot += smd[wv];   // fixed order
+      total_s = tot;
+    }
     __syncthreads();
-    server_finish<B>(a, 1, ff, &total_s);
+    server_finish<B, NT>(a, 1, ff, &total_s);
   } else {
     if (threadIdx.x == 0) {
       a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
@@ -866,16 +879,16 @@ __global__ __launch_bounds__(kThreads) void server_kernel(ServerArgs a) {
     if (!last_s) return;
     __threadfence();
     if (threadIdx.x == 0) *a.sc.srv_ticket = 0;
-    server_finish<B>(a, (int)gridDim.x, finish_fetch(a, (int)gridDim.x, false), nullptr);
+    server_finish<B, NT>(a, (int)gridDim.x, finish_fetch(a, (int)gridDim.x, false), nullptr);
   }
 }
 
 // Bookkeeping of Algorithm 2 (clocks, error norms, counters) and the new entry
 // alpha^2 ||nabla||^2 of the parameter-difference history; run by one block.
-template <int B>
+template <int B, int NT>
 __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks, const FinishFetch& f,
                                               const double* own_total) {
-  __shared__ double red[kThreads];
+  __shared__ double red[NT];
   unsigned long long my_bits = 0;
   const unsigned long long msg_bits = (B == kExact ? 0ull : 32ull) + (unsigned long long)B * (unsigned long long)a.p;
   if ((int)threadIdx.x < a.M) {                       // first chunk: already fetched
@@ -889,7 +902,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
       a.sc.t[m] = f.t + 1;
     }
   }
-  for (int m = threadIdx.x + kThreads; m < a.M; m += kThreads) {
+  for (int m = threadIdx.x + NT; m < a.M; m += NT) {
     if (a.upload[m]) {
       a.sc.Ehat2[m] = a.sc.E2[m];
       a.sc.t[m] = 0;
@@ -900,25 +913,27 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
     }
   }
   if (my_bits) atomicAdd(a.sc.bits, my_bits);
-  // ||nabla||^2: block partials summed in a fixed order (strided, then a tree)
-  double tot;
+  // ||nabla||^2: block partials summed in a fixed order (strided, then a tree); the one-block launch
+  // brings its own total
+  double total;
   if (own_total) {
-    tot = threadIdx.x == 0 ? *own_total : 0.0;
+    total = *own_total;
   } else {
-    tot = (int)threadIdx.x < n_blocks ? f.part : 0.0;
-    for (int i = threadIdx.x + kThreads; i < n_blocks; i += kThreads)
+    double tot = (int)threadIdx.x < n_blocks ? f.part : 0.0;
+    for (int i = threadIdx.x + NT; i < n_blocks; i += NT)
       tot += __hip_atomic_load(&a.sc.srv_part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  red[threadIdx.x] = tot;
-  __syncthreads();
-  for (int off = kThreads / 2; off > 0; off >>= 1) {
-    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    red[threadIdx.x] = tot;
     __syncthreads();
+    for (int off = NT / 2; off > 0; off >>= 1) {
+      if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+      __syncthreads();
+    }
+    total = red[0];
   }
   // history shift: all entries are read before any is written (one memory latency, not D)
-  const double newest = ((double)a.alpha * (double)a.alpha) * red[0];
+  const double newest = ((double)a.alpha * (double)a.alpha) * total;
   bool first = true;
-  for (int base = a.D - 1; base >= 0; base -= kThreads) {        // highest chunk first
+  for (int base = a.D - 1; base >= 0; base -= NT) {        // highest chunk first
     const int d = base - (int)threadIdx.x;                       // this thread's destination
     double v = 0.0;
     if (first) v = f.older;                                      // fetched before anything was written (used if d >= 1)
@@ -933,7 +948,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
 
 template <int B>
 __global__ __launch_bounds__(kThreads) void server_finish_kernel(ServerArgs a, int n_blocks) {
-  server_finish<B>(a, n_blocks, finish_fetch(a, n_blocks, false), nullptr);
+  server_finish<B, kThreads>(a, n_blocks, finish_fetch(a, n_blocks, false), nullptr);
 }
 
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
@@ -1038,7 +1053,9 @@ static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
 template <int B>
 static void launch_server(dim3 grid, size_t smem, hipStream_t s, const ServerArgs& a) {
   if (grid.x == 1) {
-    hipLaunchKernelGGL((server_kernel<B, true>), grid, dim3(kThreads), smem, s, a);
+    ServerArgs a1 = a;
+    a1.J = 1;                                   // 1024 lanes cover the at most 1024 groups of 8 coordinates
+    hipLaunchKernelGGL((server_kernel<B, true>), grid, dim3(kSoloThreads), smem, s, a1);
     return;
   }
   hipLaunchKernelGGL((server_kernel<B, false>), grid, dim3(kThreads), smem, s, a);

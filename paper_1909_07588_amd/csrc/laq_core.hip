@@ -143,6 +143,7 @@ __device__ __forceinline__ QuantConst quant_const(uint32_t rbits) {
 // costs microseconds; thousands of same-address atomics serialise).
 
 constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kSoloThreads = 1024;   // block size of the one-block-per-worker launches (at most 4 tiles of 256 groups)
 constexpr int kMaxSlots = 8192;   // block partials per worker
 
 struct Sweep {
@@ -340,9 +341,10 @@ __device__ __forceinline__ unsigned __int128 load_group(const uint8_t* in) {
 // bandwidth).  The block applies the skip rule itself and requests everything it will read before
 // its first wait.  The streaming instantiation stays lean: it lives on occupancy.
 template <int B, bool SOLO>
-__global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
+__global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void codes_kernel(QuantArgs a) {
+  constexpr int NT = SOLO ? kSoloThreads : kThreads;   // SOLO: sixteen wavefronts, one group of 8 coordinates per lane
   const int64_t nfull = a.p / kGroup;
-  const int64_t first = (int64_t)blockIdx.x * a.U * kThreads + threadIdx.x;
+  const int64_t first = SOLO ? (int64_t)threadIdx.x : (int64_t)blockIdx.x * a.U * kThreads + threadIdx.x;
   {
     const int m = blockIdx.y;
     const float* g = a.G + (int64_t)m * a.p_stride;
@@ -355,11 +357,11 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     } else {
       rbits = a.sc.Rfin[m];
     }
-    // SOLO: everything the block will read is requested here, before the first wait: up to four
-    // groups of g and h per thread, the ragged tail, the terms of the skip rule.  The loads are
+    // SOLO: everything the block will read is requested here, before the first wait: the lane's
+    // group of g and h, the ragged tail, the terms of the skip rule.  The loads are
     // unconditional, from clamped addresses, and their values are not touched until used.
     constexpr bool solo = SOLO;
-    const bool quick = SOLO && a.U <= 4 && nfull >= 1;
+    const bool quick = SOLO && nfull >= 1 && nfull <= NT;
     __shared__ double hterm_s[SOLO ? kMaxHistLds : 1];
     double hx = 0.0, hd = 0.0, ehat2 = 0.0;
     int t_m = 0;
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
       ehat2 = a.sc.Ehat2[m];
       t_m = a.sc.t[m];
     }
-    float4 qg[4][2], qh[4][2];
+    float4 qg[1][2], qh[1][2];
     float tg[kGroup - 1], th[kGroup - 1];          // the p % 8 coordinates after the last whole group
     if (quick) {
 #pragma unroll
@@ -377,10 +379,9 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
         const int64_t i = nfull * kGroup + k < a.p ? nfull * kGroup + k : a.p - 1;
         tg[k] = g[i]; th[k] = h[i];
       }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int64_t grp = first + (int64_t)u * kThreads;
-        grp = grp < nfull ? grp : nfull - 1;
+      {
+        constexpr int u = 0;
+        const int64_t grp = first < nfull ? first : nfull - 1;
         const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
         const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
         qg[u][0] = gp[0]; qg[u][1] = gp[1]; qh[u][0] = hp[0]; qh[u][1] = hp[1];
@@ -393,26 +394,24 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     unsigned long long accS = 0;
 
     if (quick) {
+      constexpr int u = 0;
+      const int64_t grp = first;
+      if (grp < nfull) {
+        unsigned __int128 v = 0;
+        if (!c.zero) {
+          const float gv[8] = {qg[u][0].x, qg[u][0].y, qg[u][0].z, qg[u][0].w, qg[u][1].x, qg[u][1].y, qg[u][1].z, qg[u][1].w};
+          const float hv[8] = {qh[u][0].x, qh[u][0].y, qh[u][0].z, qh[u][0].w, qh[u][1].x, qh[u][1].y, qh[u][1].z, qh[u][1].w};
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int64_t grp = first + (int64_t)u * kThreads;
-        if (u < a.U && grp < nfull) {
-          unsigned __int128 v = 0;
-          if (!c.zero) {
-            const float gv[8] = {qg[u][0].x, qg[u][0].y, qg[u][0].z, qg[u][0].w, qg[u][1].x, qg[u][1].y, qg[u][1].z, qg[u][1].w};
-            const float hv[8] = {qh[u][0].x, qh[u][0].y, qh[u][0].z, qh[u][0].w, qh[u][1].x, qh[u][1].y, qh[u][1].z, qh[u][1].w};
-#pragma unroll
-            for (int j = 0; j < kGroup; ++j)
-              v |= (unsigned __int128)quant_one<B>(gv[j], hv[j], c, sh, accN, accS) << (j * B);
-          }
-          store_group<B>(out + grp * B, v);
+          for (int j = 0; j < kGroup; ++j)
+            v |= (unsigned __int128)quant_one<B>(gv[j], hv[j], c, sh, accN, accS) << (j * B);
         }
+        store_group<B>(out + grp * B, v);
       }
     } else if (c.zero) {
-      for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads)
+      for (int64_t grp = first, u = 0; (SOLO || u < a.U) && grp < nfull; ++u, grp += NT)
         store_group<B>(out + grp * B, 0);
     } else {
-      for (int64_t grp = first, u = 0; u < a.U && grp < nfull; ++u, grp += kThreads) {
+      for (int64_t grp = first, u = 0; (SOLO || u < a.U) && grp < nfull; ++u, grp += NT) {
         const float4* gp = reinterpret_cast<const float4*>(g + grp * kGroup);
         const float4* hp = reinterpret_cast<const float4*>(h + grp * kGroup);
         const float4 g0 = gp[0], g1 = gp[1], h0 = hp[0], h1 = hp[1];
@@ -450,7 +449,7 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     }
 
     // block totals of the two exact integer sums -> slot blockIdx.x of worker m
-    __shared__ unsigned long long smS[kWavesPerBlock], smN[kWavesPerBlock];
+    __shared__ unsigned long long smS[NT / 64], smN[NT / 64];
     const unsigned long long s64 = wave_sum_u64(accS);
     const unsigned long long n64 = wave_sum_u64((unsigned long long)accN);
     if ((threadIdx.x & 63) == 0) { smS[threadIdx.x >> 6] = s64; smN[threadIdx.x >> 6] = n64; }
@@ -458,8 +457,9 @@ __global__ __launch_bounds__(kThreads) void codes_kernel(QuantArgs a) {
     if (solo) {
       if (threadIdx.x == 0) {
         constexpr int L = (1 << B) - 1;
-        const unsigned long long Sq = (smS[0] + smS[1]) + (smS[2] + smS[3]);
-        const unsigned long long N = (smN[0] + smN[1]) + (smN[2] + smN[3]);
+        unsigned long long Sq = 0, N = 0;
+#pragma unroll
+        for (int wv = 0; wv < NT / 64; ++wv) { Sq += smS[wv]; N += smN[wv]; }
         const double E2 = c.zero ? 0.0 : ldexp((double)N, 2 * (c.x - a.eps_K));
         const double r = (double)c.R / (double)L;
         const double lhs = c.zero ? 0.0 : (r * r) * (double)(long long)Sq;
@@ -650,7 +650,6 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
                                               const double* own_total);
 
 constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
-constexpr int kSoloThreads = 1024;   // block size of the one-block launches (4 tiles of 256 groups at most)
 
 // eq. 4: nabla^k = nabla^{k-1} + sum_{m in M^k} deltaQ_m, theta^{k+1} = theta^k - alpha nabla^k,
 // with Q_m(theta_hat_m) += deltaQ_m for the uploading workers (Alg. 2, upload branch).
@@ -1043,7 +1042,7 @@ static bool valid_sizes(int32_t M, int64_t p, int32_t b, int32_t D) {
 template <int B>
 static void launch_codes(dim3 grid, hipStream_t s, const QuantArgs& a) {
   if (grid.x == 1 && a.fused_decide) {
-    hipLaunchKernelGGL((codes_kernel<B, true>), grid, dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((codes_kernel<B, true>), grid, dim3(kSoloThreads), 0, s, a);
     return;
   }
   hipLaunchKernelGGL((codes_kernel<B, false>), grid, dim3(kThreads), 0, s, a);

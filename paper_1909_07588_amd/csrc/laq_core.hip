@@ -1437,20 +1437,27 @@ int laq_worker_grads_minibatch(laq_ctx* ctx, const float* theta_dev, const int32
     return set_error(ctx, LAQ_EINVAL, "laq_worker_grads_minibatch: workspace too small or misaligned (need %zu bytes)",
                      l.total);
   uint8_t* ws = static_cast<uint8_t*>(ws_dev);
-  float* Xb = reinterpret_cast<float*>(ws + l.Xb);
-  int32_t* yb = reinterpret_cast<int32_t*>(ws + l.yb);
-  const int64_t work = B * (ctx->ldx >> 2);
-  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((work + kThreads - 1) / kThreads), (unsigned)ctx->M),
-                     dim3(kThreads), 0, ctx->stream, ctx->X, ctx->y, idx_dev, ctx->N_m, ctx->ldx, B, Xb, yb,
-                     ctx->sc.status);
-  LAQ_HIP(ctx, hipGetLastError());
-  // the gradient of the loss the minibatch defines: the same kernels on the gathered rows
   const float* X0 = ctx->X; const int32_t* y0 = ctx->y; const int64_t N0 = ctx->N_m;
   uint8_t* mw0 = ctx->model_ws; const size_t mb0 = ctx->model_ws_bytes;
-  ctx->X = Xb; ctx->y = yb; ctx->N_m = B;
+  if (minibatch_reads_in_place(ctx)) {
+    // the gradient kernel follows the index list itself: no copy of the drawn rows
+    ctx->gather_idx = idx_dev; ctx->gather_rows = N0;
+  } else {
+    float* Xb = reinterpret_cast<float*>(ws + l.Xb);
+    int32_t* yb = reinterpret_cast<int32_t*>(ws + l.yb);
+    const int64_t work = B * (ctx->ldx >> 2);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((work + kThreads - 1) / kThreads), (unsigned)ctx->M),
+                       dim3(kThreads), 0, ctx->stream, ctx->X, ctx->y, idx_dev, ctx->N_m, ctx->ldx, B, Xb, yb,
+                       ctx->sc.status);
+    LAQ_HIP(ctx, hipGetLastError());
+    ctx->X = Xb; ctx->y = yb;
+  }
+  // the gradient of the loss the minibatch defines: the same kernels on the drawn rows
+  ctx->N_m = B;
   ctx->model_ws = ws + l.model; ctx->model_ws_bytes = l.total - l.model;
   const int st = laq_worker_grads(ctx, theta_dev, G_dev);
   ctx->X = X0; ctx->y = y0; ctx->N_m = N0; ctx->model_ws = mw0; ctx->model_ws_bytes = mb0;
+  ctx->gather_idx = nullptr; ctx->gather_rows = 0;
   return st;
 }
 

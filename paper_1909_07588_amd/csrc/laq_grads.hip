@@ -160,17 +160,23 @@ __device__ __forceinline__ float row_ror(float x) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xf, 0xf, false));
 }
 
-template <int TMAX>
+// GATHER (stochastic variant): the N_m rows the block range walks are the samples
+// idx[m][0..N_m) of the worker's shard of N_src rows; the tile loader takes its row from the index
+// list (requested one tile further ahead than the rows themselves), so no copy of the drawn
+// rows is made.  An index outside the shard is clamped and sets bit 1 of the status word.
+template <int TMAX, bool GATHER>
 __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
-    int64_t N_m, int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, float* __restrict__ part) {
+    int64_t N_m, int64_t N_src, const int32_t* __restrict__ idx, uint32_t* __restrict__ status,
+    int64_t ldx, int32_t F, int32_t C, int32_t rows_per_block, float* __restrict__ part) {
   constexpr int NW = kSmxWaves;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   const int m = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
-  const float* Xm = X + (int64_t)m * N_m * ldx;
-  const int32_t* ym = y + (int64_t)m * N_m;
+  const float* Xm = X + (int64_t)m * N_src * ldx;
+  const int32_t* ym = y + (int64_t)m * N_src;
+  const int32_t* idxm = GATHER ? idx + (int64_t)m * N_m : nullptr;
   const int nchunk = (F + 15) / 16;
   float* Xs = smem;                          // [2][nchunk][256]: chunk t belongs to wave t % 16
   float* Zp = Xs + 2 * nchunk * 256;         // [2][NW][64] float4: partial logits in accumulator layout
@@ -213,20 +219,48 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   const int nf4r = (F + 3) >> 2;
   float4 pre[TMAX];
   int ypre = 0;
+  // GATHER: source rows (entries of the index list) of this lane's tile row and of its softmax row,
+  // for the tile the next gload will take; requested one gload earlier
+  int ix_next = 0, iy_next = 0;
+  auto iload = [&](int64_t r0) {
+    if constexpr (GATHER) {
+      const int64_t rb = r0 < r_end ? r0 : r_end - 1;
+      const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
+      const int yrow = 4 * (wave & 3) + lq;
+      ix_next = idxm[rb + (l16 < rows_valid ? l16 : rows_valid - 1)];
+      iy_next = idxm[rb + (yrow < rows_valid ? yrow : rows_valid - 1)];
+    }
+  };
   auto gload = [&](int64_t r0, float4 (&pre)[TMAX], int& ylab) {
     // uniform tile base + 32-bit lane offsets (few address registers)
     int64_t rb = r0 < r_end ? r0 : r_end - 1;                 // first row of the tile, clamped
     const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
-    const float* base = Xm + rb * ldx;
-    const uint32_t row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
+    const float* base;
+    uint32_t row_off;
+    int64_t ysrc;
+    if constexpr (GATHER) {
+      int ix = ix_next, iy = iy_next;
+      if (ix < 0 || ix >= N_src || iy < 0 || iy >= N_src) {
+        atomicOr(status, 2u);
+        ix = ix < 0 ? 0 : (ix >= N_src ? (int)N_src - 1 : ix);
+        iy = iy < 0 ? 0 : (iy >= N_src ? (int)N_src - 1 : iy);
+      }
+      base = Xm;
+      row_off = (uint32_t)ix * (uint32_t)ldx;           // (the host checks that a shard has < 2^32 floats)
+      ysrc = iy;
+    } else {
+      base = Xm + rb * ldx;
+      row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
+      const int yrow = 4 * (wave & 3) + lq;                         // softmax waves 0..3: rows 4 wave + lq
+      ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
+    }
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
       uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;   // float4 column
       q = q < (uint32_t)nf4r ? q : 0u;
       pre[n] = *reinterpret_cast<const float4*>(base + (row_off + 4u * q));
     }
-    const int yrow = 4 * (wave & 3) + lq;                           // softmax waves 0..3: rows 4 wave + lq
-    ylab = ym[rb + (yrow < rows_valid ? yrow : rows_valid - 1)];
+    ylab = ym[ysrc];
   };
 
   floatx4 acc2[TMAX];
@@ -310,10 +344,13 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   // row and the results are never used (under branches the compiler merges register sets with
   // copies and waits for loads right after issuing them: a memory latency per tile).
   if (r_begin >= r_end) return;                     // (uniform; cannot happen with the host's grid)
+  iload(r_begin);
   gload(r_begin, pre, ypre);
+  iload(r_begin + kRT);
   consume(pre, 0);
   int ycur = ypre;                                  // labels of this lane's softmax row in the tile of Zp[0]
   gload(r_begin + kRT, pre, ypre);
+  iload(r_begin + 2 * kRT);
   int buf = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
     __syncthreads();                                // Zp[buf] complete; Zp[buf ^ 1] and slice buffer buf ^ 1 free
@@ -325,6 +362,7 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     consume(pre, buf ^ 1);
     const int ynext = ypre;
     gload(r0 + 2 * kRT, pre, ypre);
+    iload(r0 + 3 * kRT);
     __syncthreads();                                // Rs[buf] complete
     rank_update(buf);
     ycur = ynext;
@@ -476,6 +514,13 @@ static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block)
   return (int)((N_m + rpb - 1) / rpb);
 }
 
+// The matrix-core softmax kernel can take a minibatch's rows straight from the bound data through
+// the index list (32-bit float offsets inside a shard).
+bool minibatch_reads_in_place(const laq_ctx* ctx) {
+  return ctx->kind == LAQ_MODEL_SOFTMAX && softmax_mfma_lds(ctx) != 0 &&
+         (uint64_t)ctx->N_m * (uint64_t)ctx->ldx < (1ull << 32);
+}
+
 static bool logistic_supported(const laq_ctx* ctx) {
   const int kf = (ctx->F + 63) / 64;
   if (ctx->kind == LAQ_MODEL_BINLOG) return kf <= 16;
@@ -522,11 +567,12 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     const int nchunk = (ctx->F + 15) / 16;
 #define LAQ_SMM(T)                                                                                     \
   do {                                                                                                 \
-    auto kfn = softmax_grad_mfma_kernel<T>;                                                            \
+    auto kfn = ctx->gather_idx ? softmax_grad_mfma_kernel<T, true> : softmax_grad_mfma_kernel<T, false>; \
     LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                               \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
     hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta, ctx->X, ctx->y,   \
-                       ctx->N_m, ctx->ldx, ctx->F, ctx->C, rpb, part);                                  \
+                       ctx->N_m, ctx->gather_idx ? ctx->gather_rows : ctx->N_m, ctx->gather_idx,        \
+                       ctx->sc.status, ctx->ldx, ctx->F, ctx->C, rpb, part);                            \
   } while (0)
     if (nchunk <= kSmxWaves) LAQ_SMM(1);
     else if (nchunk <= 2 * kSmxWaves) LAQ_SMM(2);

@@ -64,6 +64,10 @@ struct laq_ctx {
   // kernels' epilogues leave block maxima of |g - h| in rprod[m][0..rprod_count);
   // valid only for the G pointer in radius_for and until the state changes.
   const float* radius_for = nullptr;
+  // Minibatch call in flight: the matrix-core softmax kernel reads the drawn rows through this
+  // index list [M][N_m] from shards of gather_rows rows (else nullptr).
+  const int32_t* gather_idx = nullptr;
+  int64_t gather_rows = 0;
   uint32_t* rprod = nullptr;
   int32_t rprod_stride = 0, rprod_count = 0;
 
@@ -96,5 +100,6 @@ int set_error(laq_ctx* ctx, int status, const char* fmt, ...);
 // gradient kernels (laq_grads.hip)
 size_t model_workspace_bytes(const laq_ctx* ctx, int64_t N_m);
 int worker_grads(laq_ctx* ctx, const float* theta, float* G);
+bool minibatch_reads_in_place(const laq_ctx* ctx);
 
 }  // namespace laq

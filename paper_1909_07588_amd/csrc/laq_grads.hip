@@ -164,7 +164,10 @@ __device__ __forceinline__ float row_ror(float x) {
 // idx[m][0..N_m) of the worker's shard of N_src rows; the tile loader takes its row from the index
 // list (requested one tile further ahead than the rows themselves), so no copy of the drawn
 // rows is made.  An index outside the shard is clamped and sets bit 1 of the status word.
-template <int TMAX, bool GATHER>
+// NFULL = nchunk / 16: the chunks w + 16 n, n < NFULL, exist for every wave w and lie wholly inside
+// the F columns, so their code is straight-line (no branch, no column mask, LDS and global
+// addresses = one lane base + a constant per n); only the chunks n >= NFULL depend on the wave.
+template <int TMAX, int NFULL, bool GATHER>
 __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
     int64_t N_m, int64_t N_src, const int32_t* __restrict__ idx, uint32_t* __restrict__ status,
@@ -172,7 +175,8 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   constexpr int NW = kSmxWaves;
   extern __shared__ __attribute__((aligned(16))) float smem[];
   const int m = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (uniform: branches on it are scalar)
   const int l16 = lane & 15, lq = lane >> 4;
   const float* Xm = X + (int64_t)m * N_src * ldx;
   const int32_t* ym = y + (int64_t)m * N_src;
@@ -231,13 +235,20 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
       iy_next = idxm[rb + (yrow < rows_valid ? yrow : rows_valid - 1)];
     }
   };
-  auto gload = [&](int64_t r0, float4 (&pre)[TMAX], int& ylab) {
-    // uniform tile base + 32-bit lane offsets (few address registers)
-    int64_t rb = r0 < r_end ? r0 : r_end - 1;                 // first row of the tile, clamped
-    const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
+  // Where the tile starting at row r0 lies: a per-lane pointer to the lane's 16 bytes of chunk
+  // `wave` (chunk w + 16 n lies 1 KB further per n), the pieces for a chunk that may cross column F,
+  // and the row of this lane's label.
+  struct TileAddr {
+    const float* lanep;
     const float* base;
     uint32_t row_off;
     int64_t ysrc;
+  };
+  auto gaddr = [&](int64_t r0) {
+    // uniform tile base + 32-bit lane offsets (few address registers)
+    int64_t rb = r0 < r_end ? r0 : r_end - 1;                 // first row of the tile, clamped
+    const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
+    TileAddr A;
     if constexpr (GATHER) {
       int ix = ix_next, iy = iy_next;
       if (ix < 0 || ix >= N_src || iy < 0 || iy >= N_src) {
@@ -245,22 +256,23 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
         ix = ix < 0 ? 0 : (ix >= N_src ? (int)N_src - 1 : ix);
         iy = iy < 0 ? 0 : (iy >= N_src ? (int)N_src - 1 : iy);
       }
-      base = Xm;
-      row_off = (uint32_t)ix * (uint32_t)ldx;           // (the host checks that a shard has < 2^32 floats)
-      ysrc = iy;
+      A.base = Xm;
+      A.row_off = (uint32_t)ix * (uint32_t)ldx;         // (the host checks that a shard has < 2^32 floats)
+      A.ysrc = iy;
     } else {
-      base = Xm + rb * ldx;
-      row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
+      A.base = Xm + rb * ldx;
+      A.row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
       const int yrow = 4 * (wave & 3) + lq;                         // softmax waves 0..3: rows 4 wave + lq
-      ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
+      A.ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
     }
-#pragma unroll
-    for (int n = 0; n < TMAX; ++n) {
-      uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;   // float4 column
-      q = q < (uint32_t)nf4r ? q : 0u;
-      pre[n] = *reinterpret_cast<const float4*>(base + (row_off + 4u * q));
-    }
-    ylab = ym[ysrc];
+    A.lanep = A.base + (A.row_off + 4u * (4u * (uint32_t)wave + (uint32_t)lq));
+    return A;
+  };
+  auto gchunk = [&](int n, const TileAddr& A) {
+    if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 16 * NW * n);
+    uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;     // float4 column
+    q = q < (uint32_t)nf4r ? q : 0u;
+    return *reinterpret_cast<const float4*>(A.base + (A.row_off + 4u * q));
   };
 
   floatx4 acc2[TMAX];
@@ -268,15 +280,25 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   for (int n = 0; n < TMAX; ++n) acc2[n] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   // logits of the tile in pre -> Zp[buf][wave]; the tile -> this wave's LDS slice of buffer buf
-  auto consume = [&](const float4 (&pre)[TMAX], int buf) {
+  // Each chunk's registers are refilled from the tile at `next` as soon as the chunk is used: the
+  // 64 loads a CU issues per tile then reach the address unit spread over the whole step (issued in
+  // one burst they held every wave at its last load for up to 1.3 us, right before a barrier).
+  auto consume = [&](float4 (&pre)[TMAX], int buf, const TileAddr& next) {
     floatx4 za = floatx4{0.f, 0.f, 0.f, 0.f}, zb = floatx4{0.f, 0.f, 0.f, 0.f};
-    float* Xb = Xs + buf * nchunk * 256;
+    float* xw = Xs + (buf * nchunk + wave) * 256 + wr_off;     // this lane's 16 bytes of chunk `wave`
 #pragma unroll
     for (int n = 0; n < TMAX; ++n) {
-      const int t = wave + NW * n;
-      if (t < nchunk) {                                       // uniform over the wave
+      if (n < NFULL) {
+        const float4 a = pre[n];
+        za = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, thf[n].x, za, 0, 0, 0);
+        zb = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, zb, 0, 0, 0);
+        za = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, thf[n].z, za, 0, 0, 0);
+        zb = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, zb, 0, 0, 0);
+        *reinterpret_cast<float4*>(xw + NW * 256 * n) = a;
+        pre[n] = gchunk(n, next);
+      } else if (wave + NW * n < nchunk) {                    // uniform over the wave
         float4 a = pre[n];
-        const int f = 16 * t + 4 * lq;
+        const int f = 16 * (wave + NW * n) + 4 * lq;
         a.x = f < F ? a.x : 0.0f;
         a.y = f + 1 < F ? a.y : 0.0f;
         a.z = f + 2 < F ? a.z : 0.0f;
@@ -285,7 +307,8 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
         zb = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, thf[n].y, zb, 0, 0, 0);
         za = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, thf[n].z, za, 0, 0, 0);
         zb = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, thf[n].w, zb, 0, 0, 0);
-        *reinterpret_cast<float4*>(&Xb[t * 256 + wr_off]) = a;
+        *reinterpret_cast<float4*>(xw + NW * 256 * n) = a;
+        pre[n] = gchunk(n, next);
       }
     }
     za = za + zb;
@@ -319,51 +342,64 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   };
   // rank-16 update with the tile parked in buffer buf
   auto rank_update = [&](int buf) {
-    const float* Xb = Xs + buf * nchunk * 256;
+    const float* xw = Xs + (buf * nchunk + wave) * 256;
     float ar[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) ar[u] = Rs[buf * 256 + (4 * u + lq) * 16 + l16];
+    // whole chunks first: their reads are issued together and the matrix instructions of different
+    // chunks (independent accumulators) alternate
+    float bf[NFULL > 0 ? NFULL : 1][4];
 #pragma unroll
-    for (int n = 0; n < TMAX; ++n) {
-      const int t = wave + NW * n;
-      if (t < nchunk) {
+    for (int n = 0; n < NFULL; ++n)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) bf[n][u] = xw[NW * 256 * n + rd_off[u]];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int n = 0; n < NFULL; ++n)
+        acc2[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[u], bf[n][u], acc2[n], 0, 0, 0);
+#pragma unroll
+    for (int n = NFULL; n < TMAX; ++n) {
+      if (wave + NW * n < nchunk) {                           // uniform over the wave
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float b = Xb[t * 256 + rd_off[u]];
+          const float b = xw[NW * 256 * n + rd_off[u]];
           acc2[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[u], b, acc2[n], 0, 0, 0);
         }
       }
     }
   };
 
-  // Pipeline for tile n: [barrier: partial logits of tile n complete] waves 0..3 (one per SIMD)
-  // turn them into residuals; every wave forms the logits of tile n+1 from its registers, which
-  // then take tile n+2 (in flight for the rest of the step); [barrier: residuals complete] rank
-  // update with tile n.  The logits step parks tile n+1 in the slice buffer the update is not
-  // using.  Everything is unconditional: past the block's range the loads are clamped to its last
-  // row and the results are never used (under branches the compiler merges register sets with
+  // Pipeline for tile n: [barrier: partial logits of tile n complete] waves 0..3 turn them into
+  // residuals while the others wait (their matrix instructions would slip in between the dependent
+  // vector instructions of the softmax and stretch it threefold); [barrier: residuals complete]
+  // every wave forms the logits of tile n+1 from its registers, refilling them chunk by chunk with
+  // tile n+2, and goes straight on to the rank update with tile n, whose slice it parked itself one
+  // step earlier.  Everything is unconditional: past the block's range the loads are clamped to its
+  // last row and the results are never used (under branches the compiler merges register sets with
   // copies and waits for loads right after issuing them: a memory latency per tile).
   if (r_begin >= r_end) return;                     // (uniform; cannot happen with the host's grid)
   iload(r_begin);
-  gload(r_begin, pre, ypre);
+  TileAddr A = gaddr(r_begin);
+#pragma unroll
+  for (int n = 0; n < TMAX; ++n) pre[n] = gchunk(n, A);
+  ypre = ym[A.ysrc];
   iload(r_begin + kRT);
-  consume(pre, 0);
+  A = gaddr(r_begin + kRT);
+  consume(pre, 0, A);
   int ycur = ypre;                                  // labels of this lane's softmax row in the tile of Zp[0]
-  gload(r_begin + kRT, pre, ypre);
+  ypre = ym[A.ysrc];
   iload(r_begin + 2 * kRT);
   int buf = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
     __syncthreads();                                // Zp[buf] complete; Zp[buf ^ 1] and slice buffer buf ^ 1 free
-    if (wave < 4) {                                 // uniform over the wave
-      __builtin_amdgcn_s_setprio(2);                // the wave with the extra work goes first
-      softmax_rows(buf, r0, ycur);
-      __builtin_amdgcn_s_setprio(0);
-    }
-    consume(pre, buf ^ 1);
-    const int ynext = ypre;
-    gload(r0 + 2 * kRT, pre, ypre);
-    iload(r0 + 3 * kRT);
+    if (wave < 4) softmax_rows(buf, r0, ycur);      // uniform over the wave
     __syncthreads();                                // Rs[buf] complete
+    A = gaddr(r0 + 2 * kRT);
+    const int ynext = ypre;
+    consume(pre, buf ^ 1, A);
+    ypre = ym[A.ysrc];
+    iload(r0 + 3 * kRT);
     rank_update(buf);
     ycur = ynext;
     buf ^= 1;
@@ -565,18 +601,22 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   const size_t mfma_lds = softmax_mfma_lds(ctx);
   if (mfma_lds) {
     const int nchunk = (ctx->F + 15) / 16;
-#define LAQ_SMM(T)                                                                                     \
+#define LAQ_SMM(T, NF)                                                                                 \
   do {                                                                                                 \
-    auto kfn = ctx->gather_idx ? softmax_grad_mfma_kernel<T, true> : softmax_grad_mfma_kernel<T, false>; \
+    auto kfn = ctx->gather_idx ? softmax_grad_mfma_kernel<T, NF, true> : softmax_grad_mfma_kernel<T, NF, false>; \
     LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                               \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
     hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta, ctx->X, ctx->y,   \
                        ctx->N_m, ctx->gather_idx ? ctx->gather_rows : ctx->N_m, ctx->gather_idx,        \
                        ctx->sc.status, ctx->ldx, ctx->F, ctx->C, rpb, part);                            \
   } while (0)
-    if (nchunk <= kSmxWaves) LAQ_SMM(1);
-    else if (nchunk <= 2 * kSmxWaves) LAQ_SMM(2);
-    else LAQ_SMM(4);
+    // chunks n < nfull exist for every wave and hold no column >= F
+    const int nfull = (ctx->F / 16) / kSmxWaves;
+    if (nchunk <= kSmxWaves) { if (nfull >= 1) LAQ_SMM(1, 1); else LAQ_SMM(1, 0); }
+    else if (nchunk <= 2 * kSmxWaves) { if (nfull >= 2) LAQ_SMM(2, 2); else LAQ_SMM(2, 1); }
+    else if (nfull >= 4) LAQ_SMM(4, 4);
+    else if (nfull == 3) LAQ_SMM(4, 3);
+    else LAQ_SMM(4, 2);
 #undef LAQ_SMM
   } else if (ctx->kind == LAQ_MODEL_SOFTMAX) {
     if (kf <= 1) launch_softmax<1>(ctx, grid, theta, rpb, part);

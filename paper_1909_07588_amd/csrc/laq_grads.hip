@@ -135,18 +135,20 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
 // rows.  Wave w owns the feature chunks w, w+16, ... of 16 columns in BOTH
 // products, so its slice of every tile is private to it:
 //   * it loads the slice straight from HBM in the A-operand layout of the
-//     logits (lane = row, 4 consecutive columns), one tile ahead;
+//     logits (lane = row, 4 consecutive columns), two tiles ahead;
 //   * the logits' matrix instructions take these registers directly and leave
 //     the wave's partial product in LDS (Zp);
 //   * the registers are then parked in the wave's own LDS slice, from which the
 //     rank-16 update reads them back in its B-operand layout (lane = column);
 //     no other wave touches the slice, so no barrier guards it.
-// The block meets twice per tile: once after the partial logits are written and
-// once after the residuals R = softmax(Z) - onehot(y) are.  The softmax runs on
-// four waves, one per SIMD, each lane holding one of the 256 entries: measured
-// here, vector instructions and matrix instructions of the waves on a SIMD do
-// not overlap much, so the softmax is kept to as few wave instructions as
-// possible, given priority, and the other twelve waves multiply meanwhile.
+// The block meets twice per tile, before and after the softmax, which four
+// waves (one per SIMD, each lane holding one of the 256 entries) compute while
+// the others wait: on a SIMD, vector and matrix instructions do not run in the
+// same cycles, and with other waves' matrix instructions slipping in between
+// its dependent vector instructions the softmax took twice as long.  After the
+// second barrier every wave forms the logits of the next tile, refills each
+// chunk's registers as soon as the chunk is used (a burst of loads stalls the
+// waves in the CU's load queue) and goes straight on to the rank update.
 // Theta fragments and the wave's part of Gacc stay in registers for the whole
 // kernel.  LDS (two slice buffers, two partial-logit buffers: about 135 KB) and
 // registers allow one block per CU.

@@ -245,6 +245,35 @@ def test_softmax_gradient_shapes(F, C, N_m, M):
     assert err.max() <= 1e-5, err
 
 
+@pytest.mark.parametrize("F,C", [(100, 3), (256, 10), (300, 16), (512, 5), (600, 10), (785, 10), (1024, 2)])
+def test_softmax_gradient_every_chunk_layout_full_batch_and_minibatch(F, C):
+    """Feature counts on both sides of every boundary of the matrix-core kernel's chunk bookkeeping
+    (16 waves x 16 columns: 256, 512, 768), several tiles per block with a ragged last tile, and the
+    same shapes through the index list of the stochastic variant (with an out-of-order draw)."""
+    M, N_m, B = 8, 1100, 700
+    w = laq_synth.Workload("t", 2, laq_synth.KIND_SOFTMAX, M, N_m, (F, C), F * C, 4)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    rng = np.random.default_rng(F * 31 + C)
+    theta_h = (theta0 + 0.05 * rng.standard_normal(w.p)).astype(np.float32)
+    ctx, st, _ = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta_h)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    theta = torch.from_numpy(theta_h).to(DEV)
+    Gd = ctx.alloc_G()
+    ctx.laq_worker_grads(theta, Gd)
+    torch.cuda.synchronize()
+    G_ref, _ = oracle.grads_all(w.kind, theta_h, X, y, w.dims, w.lam)
+    G = Gd[:, :w.p].cpu().numpy()
+    assert (np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)).max() <= 1e-5
+    idx = laq_synth.minibatch_indices(w, B, 3)
+    ctx.laq_worker_grads_minibatch(theta, torch.from_numpy(idx).to(DEV), Gd)
+    torch.cuda.synchronize()
+    G_ref = oracle.grads_minibatch(w.kind, theta_h, X, y, w.dims, w.lam, idx)
+    G = Gd[:, :w.p].cpu().numpy()
+    assert (np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)).max() <= 1e-5
+    assert ctx.laq_get_counters()[2] == 0
+
+
 def test_full_loop_on_the_smallest_workload():
     """Config 1, all four steps on the GPU, teacher-forced: the oracle quantizes
     the GPU's gradients (compared to its own within 1e-5) from the same state."""

@@ -245,10 +245,11 @@ def test_softmax_gradient_shapes(F, C, N_m, M):
     assert err.max() <= 1e-5, err
 
 
-@pytest.mark.parametrize("F,C", [(100, 3), (256, 10), (300, 16), (512, 5), (600, 10), (785, 10), (1024, 2)])
+@pytest.mark.parametrize("F,C", [(100, 3), (256, 10), (300, 16), (512, 5), (600, 10), (785, 10), (1000, 4), (1024, 2)])
 def test_softmax_gradient_every_chunk_layout_full_batch_and_minibatch(F, C):
     """Feature counts on both sides of every boundary of the matrix-core kernel's chunk bookkeeping
-    (16 waves x 16 columns: 256, 512, 768), several tiles per block with a ragged last tile, and the
+    (16 waves x 16 columns: 256, 512, 768; 1000 columns fill the 160 KB of LDS to the byte), several tiles
+    per block with a ragged last tile, and the
     same shapes through the index list of the stochastic variant (with an out-of-order draw)."""
     M, N_m, B = 8, 1100, 700
     w = laq_synth.Workload("t", 2, laq_synth.KIND_SOFTMAX, M, N_m, (F, C), F * C, 4)

@@ -156,6 +156,7 @@ struct FastLoader {
   int kk[NV];           // its k offset inside the tile
   bool xin[NV];         // its row/column lies inside the operand (false for a float4 that does not exist)
   int64_t kstep;        // address advance per K tile
+  int64_t kunit;        // address advance per unit of k
   int K;
   bool all_in;          // the whole block tile lies inside the operand (uniform over the block)
 
@@ -174,9 +175,12 @@ struct FastLoader {
       q[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
     }
     kstep = XMAJOR ? BK : (int64_t)BK * ld;
+    kunit = XMAJOR ? 1 : ld;
   }
   // Loads K tile number `tile` (tiles are requested in order 0, 1, 2, ...) and advances the
-  // pointers.  In the last, partial tile, rows of k >= K are redirected to tile 0 (in bounds).
+  // pointers.  In the last, partial tile, a float4 of k >= K is redirected to k = 0 .. 3 of its own
+  // row or column, which is inside the operand whatever K (K >= 4 on this path; its place in tile 0
+  // would not be when K < BK and the first tile is itself the partial one).
   // Nothing here touches the loaded values, so the wave does not wait for them before it multiplies.
   __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) {
     const int k0 = tile * BK;
@@ -190,7 +194,7 @@ struct FastLoader {
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const bool kin = k0 + kk[i] < K;
-        r[i] = *reinterpret_cast<const float4*>(kin ? q[i] : q[i] - (int64_t)tile * kstep);
+        r[i] = *reinterpret_cast<const float4*>(kin ? q[i] : q[i] - (int64_t)tile * kstep - kk[i] * kunit);
       }
     }
   }

@@ -302,7 +302,10 @@ def test_full_loop_on_the_smallest_workload():
 
 @pytest.mark.parametrize("dims,N_m,M", [((20, 16, 12, 5), 33, 2), ((30, 7), 50, 3), ((784, 200, 10), 300, 3),
                                         ((130, 257, 129, 10), 259, 2), ((64, 128, 16), 128, 1),
-                                        ((784, 512, 256, 10), 512, 2)])
+                                        ((784, 512, 256, 10), 512, 2),
+                                        # widths of 4, 8 and 12 on the aligned loaders: a contraction shorter
+                                        # than one K tile of the matrix kernel
+                                        ((8, 12, 4, 5), 64, 2), ((4, 8, 3), 32, 1), ((12, 16, 8, 4, 2), 100, 3)])
 def test_mlp_gradients_match_the_oracle(dims, N_m, M):
     w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, M, N_m, dims, laq_synth.mlp_param_count(dims), 8)
     G, G_ref = _grad_case(w)

@@ -61,6 +61,11 @@ def run_model_workload(w, steps, warmup, phase_steps=100, minibatch=0):
     ctx.laq_set_model(w.kind, w.dims, w.lam)
     Xd, yd = torch.from_numpy(X).to(dev), torch.from_numpy(y).to(dev)
     ctx.laq_set_data(Xd, yd)
+    # the samples are fixed for the whole run: laid out once (untimed, like the upload of X itself)
+    # for the kernel that reads them in every iteration, where the library has such a layout
+    tiled = not minibatch and ctx.laq_tiled_data_bytes() > 0
+    if tiled:
+        ctx.laq_tile_data()
     theta = torch.from_numpy(theta0.copy()).to(dev)
     G = ctx.alloc_G()
     codes, R, up = ctx.alloc_messages()
@@ -109,7 +114,7 @@ def run_model_workload(w, steps, warmup, phase_steps=100, minibatch=0):
     it_total = warmup + steps
     res = {
         "workload": w.name + (f"_slaq_B{minibatch}" if minibatch else ""), "M": w.M, "N_m": w.N_m, "p": w.p,
-        "b": w.b, "steps": steps,
+        "b": w.b, "steps": steps, "x_layout": "tiles of 16 rows (laq_tile_data)" if tiled else "row-major",
         "iterations_per_s": round(steps / (total_ms * 1e-3), 2), "ms_per_step": round(total_ms / steps, 5),
         "phase_ms": {"worker_grads": round(ph[0], 5), "quantize_skip": round(ph[1], 5),
                      "server_step": round(ph[2], 5)},
@@ -252,6 +257,7 @@ def modes_table(iters=500):
             ctx.laq_set_mode(laq.MODE_FORCE_UPLOAD)
         ctx.laq_set_model(w.kind, w.dims, w.lam)
         ctx.laq_set_data(Xd, yd)
+        ctx.laq_tile_data()
         theta = torch.from_numpy(theta0.copy()).to(dev)
         G = ctx.alloc_G()
         codes, R, up = ctx.alloc_messages()

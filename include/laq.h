@@ -136,6 +136,24 @@ int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t
                  int64_t ldx, void* model_ws_dev, size_t model_ws_bytes);
 
 /*
+ * Optional, for the SOFTMAX model.  Worker m evaluates grad f_m on the same
+ * local samples in every iteration (Algorithm 2; f_m of eq. 1 is fixed), so
+ * the samples can be laid out once for the kernel that reads them in every
+ * iteration: laq_tile_data copies the bound X into tiled_dev (caller-owned
+ * device memory, 256-byte aligned, at least laq_tiled_data_bytes(ctx) bytes,
+ * alive while the data stay bound) as tiles of 16 rows, each one contiguous
+ * run of 16-column chunks padded with zeros.  The copy is enqueued on the
+ * stream; from then on laq_worker_grads reads tiled_dev instead of X_dev
+ * (same arithmetic, same results), and later changes of X_dev are not seen
+ * until laq_tile_data is called again.  laq_worker_grads_minibatch keeps
+ * reading X_dev, which must stay alive.  laq_set_model and laq_set_data drop
+ * the copy.  laq_tiled_data_bytes returns 0 when the bound model and data
+ * have no kernel that reads tiles (then laq_tile_data returns LAQ_EINVAL).
+ */
+size_t laq_tiled_data_bytes(const laq_ctx* ctx);
+int laq_tile_data(laq_ctx* ctx, void* tiled_dev, size_t tiled_bytes);
+
+/*
  * Algorithm 2, worker step, first half: G_dev[m][0..p) = grad f_m(theta) for
  * all M workers (fp32 arithmetic; row stride laq_p_stride(p)).
  * theta_dev[p] is read only.  Needs laq_set_model and laq_set_data.

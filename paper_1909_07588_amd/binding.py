@@ -14,7 +14,7 @@ B_EXACT = 32          # laq_create's b for the identity quantizer (LAG / GD)
 
 EXPORTS = ["laq_p_stride", "laq_w_stride", "laq_workspace_bytes", "laq_create", "laq_destroy",
            "laq_reset", "laq_set_mode", "laq_set_model", "laq_model_workspace_bytes",
-           "laq_set_data", "laq_worker_grads", "laq_minibatch_workspace_bytes",
+           "laq_set_data", "laq_tiled_data_bytes", "laq_tile_data", "laq_worker_grads", "laq_minibatch_workspace_bytes",
            "laq_worker_grads_minibatch", "laq_quantize_skip", "laq_radius_handover", "laq_server_step",
            "laq_get_state", "laq_get_counters", "laq_last_error"]
 
@@ -67,6 +67,10 @@ def lib():
         L.laq_model_workspace_bytes.argtypes = [vp, i64]
         L.laq_set_data.restype = C.c_int
         L.laq_set_data.argtypes = [vp, vp, vp, i64, i64, vp, sz]
+        L.laq_tiled_data_bytes.restype = sz
+        L.laq_tiled_data_bytes.argtypes = [vp]
+        L.laq_tile_data.restype = C.c_int
+        L.laq_tile_data.argtypes = [vp, vp, sz]
         L.laq_worker_grads.restype = C.c_int
         L.laq_worker_grads.argtypes = [vp, vp, vp]
         L.laq_minibatch_workspace_bytes.restype = sz
@@ -211,6 +215,18 @@ class Laq:
         self._keep = [X, y]
         self._chk(self.L.laq_set_data(self.h, C.c_void_p(X.data_ptr()), C.c_void_p(y.data_ptr()), N_m, ldx,
                                       C.c_void_p(self._model_ws.data_ptr() + off), need))
+
+    def laq_tiled_data_bytes(self):
+        return int(self.L.laq_tiled_data_bytes(self.h))
+
+    def laq_tile_data(self):
+        """Allocates the tiled copy of the bound X (kept alive here) and hands it to the library."""
+        need = self.laq_tiled_data_bytes()
+        if need == 0:
+            raise LaqError("laq_tile_data: the bound model and data have no kernel that reads tiles")
+        self._tiled = self.torch.empty(need + 256, dtype=self.torch.uint8, device=self.device)
+        off = (-self._tiled.data_ptr()) % 256
+        self._chk(self.L.laq_tile_data(self.h, C.c_void_p(self._tiled.data_ptr() + off), need))
 
     def laq_worker_grads(self, theta, G):
         self._chk(self.L.laq_worker_grads(self.h, C.c_void_p(theta.data_ptr()), C.c_void_p(G.data_ptr())))

@@ -1377,6 +1377,7 @@ int laq_set_model(laq_ctx* ctx, int32_t kind, const int32_t* dims, int32_t n_dim
   ctx->lambda = lambda;
   ctx->radius_for = nullptr;
   ctx->X = nullptr; ctx->y = nullptr; ctx->model_ws = nullptr;
+  ctx->Xtiled = nullptr; ctx->tiled_for = nullptr; ctx->tiled_rows = 0;
   return LAQ_OK;
 }
 
@@ -1396,6 +1397,26 @@ int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t
     return set_error(ctx, LAQ_EINVAL, "laq_set_data: model workspace too small or misaligned (need %zu bytes)", need);
   ctx->X = X_dev; ctx->y = y_dev; ctx->N_m = N_m; ctx->ldx = ldx;
   ctx->model_ws = (uint8_t*)model_ws_dev; ctx->model_ws_bytes = model_ws_bytes;
+  ctx->Xtiled = nullptr; ctx->tiled_for = nullptr; ctx->tiled_rows = 0;
+  return LAQ_OK;
+}
+
+size_t laq_tiled_data_bytes(const laq_ctx* ctx) {
+  if (!ctx || ctx->kind == LAQ_MODEL_NONE) return 0;
+  return tiled_data_bytes(ctx);
+}
+
+int laq_tile_data(laq_ctx* ctx, void* tiled_dev, size_t tiled_bytes) {
+  if (!ctx) return LAQ_EINVAL;
+  if (ctx->kind == LAQ_MODEL_NONE || !ctx->X)
+    return set_error(ctx, LAQ_ESTATE, "laq_tile_data needs laq_set_model and laq_set_data");
+  const size_t need = tiled_data_bytes(ctx);
+  if (need == 0) return set_error(ctx, LAQ_EINVAL, "laq_tile_data: this model has no kernel that reads tiled data");
+  if (!tiled_dev || tiled_bytes < need || ((uintptr_t)tiled_dev & 255))
+    return set_error(ctx, LAQ_EINVAL, "laq_tile_data: buffer too small or misaligned (need %zu bytes)", need);
+  const int st = tile_data(ctx, static_cast<float*>(tiled_dev));
+  if (st != LAQ_OK) return st;
+  ctx->Xtiled = static_cast<const float*>(tiled_dev); ctx->tiled_for = ctx->X; ctx->tiled_rows = ctx->N_m;
   return LAQ_OK;
 }
 

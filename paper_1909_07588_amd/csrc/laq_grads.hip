@@ -169,7 +169,16 @@ __device__ __forceinline__ float row_ror(float x) {
 // NFULL = nchunk / 16: the chunks w + 16 n, n < NFULL, exist for every wave w and lie wholly inside
 // the F columns, so their code is straight-line (no branch, no column mask, LDS and global
 // addresses = one lane base + a constant per n); only the chunks n >= NFULL depend on the wave.
-template <int TMAX, int NFULL, bool GATHER>
+//
+// SRC says where the rows come from: kSrcRows = the caller's row-major matrix; kSrcGather = the same
+// through the index list; kSrcTiled = the tiled copy that tile_rows_kernel writes (a tile one
+// contiguous run of nchunk KB, chunk t its t-th KB with lane l's 16 bytes at byte 16 l, zeros past row
+// N_m and column F).  From the tiled copy a wave-wide load is one contiguous KB instead of 16 pieces
+// of 64 bytes a row apart, which the memory system serves a little faster (42 instead of 44 us on
+// the 785-column workload).
+constexpr int kSrcRows = 0, kSrcGather = 1, kSrcTiled = 2;
+
+template <int TMAX, int NFULL, int SRC>
 __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     const float* __restrict__ theta, const float* __restrict__ X, const int32_t* __restrict__ y,
     int64_t N_m, int64_t N_src, const int32_t* __restrict__ idx, uint32_t* __restrict__ status,
@@ -180,10 +189,12 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (uniform: branches on it are scalar)
   const int l16 = lane & 15, lq = lane >> 4;
-  const float* Xm = X + (int64_t)m * N_src * ldx;
+  constexpr bool GATHER = SRC == kSrcGather, TILED = SRC == kSrcTiled;
+  const int nchunk = (F + 15) / 16;
+  const float* Xm = TILED ? X + (int64_t)m * ((N_src + kRT - 1) / kRT) * ((int64_t)nchunk * 256)
+                          : X + (int64_t)m * N_src * ldx;
   const int32_t* ym = y + (int64_t)m * N_src;
   const int32_t* idxm = GATHER ? idx + (int64_t)m * N_m : nullptr;
-  const int nchunk = (F + 15) / 16;
   float* Xs = smem;                          // [2][nchunk][256]: chunk t belongs to wave t % 16
   float* Zp = Xs + 2 * nchunk * 256;         // [2][NW][64] float4: partial logits in accumulator layout
   float* Rs = Zp + 2 * NW * 256;             // [2][16][16] residuals P - Y
@@ -261,6 +272,13 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
       A.base = Xm;
       A.row_off = (uint32_t)ix * (uint32_t)ldx;         // (the host checks that a shard has < 2^32 floats)
       A.ysrc = iy;
+    } else if constexpr (TILED) {
+      A.base = Xm + (rb / kRT) * ((int64_t)nchunk * 256);           // (blocks start on tile boundaries)
+      A.row_off = 0;
+      const int yrow = 4 * (wave & 3) + lq;
+      A.ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
+      A.lanep = A.base + 4 * lane;                                  // the lane's 16 bytes of chunk 0
+      return A;
     } else {
       A.base = Xm + rb * ldx;
       A.row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
@@ -271,6 +289,12 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     return A;
   };
   auto gchunk = [&](int n, const TileAddr& A) {
+    if constexpr (TILED) {
+      // chunk c lies c KB into the tile; a chunk past the tile's last one reads chunk 0 instead
+      const int c = wave + NW * n;
+      if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 256 * c);
+      return *reinterpret_cast<const float4*>(A.lanep + 256 * (c < nchunk ? c : 0));
+    }
     if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 16 * NW * n);
     uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;     // float4 column
     q = q < (uint32_t)nf4r ? q : 0u;
@@ -518,6 +542,33 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
     rprod[(int64_t)m * gridDim.x + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
+// Tiled copy of the bound rows for softmax_grad_mfma_kernel<.., kSrcTiled>: worker m, tile T (16 rows),
+// chunk t (16 columns) -> 256 floats at ((m tiles + T) nchunk + t) 256; float 4 l + j of a chunk is
+// X[16 T + l % 16][16 t + 4 (l / 16) + j] (the kernel's lane l holds row l % 16, quarter l / 16 of a
+// chunk), zero past row N_m or column F.  One thread per 16 bytes.
+__global__ __launch_bounds__(kThreads) void tile_rows_kernel(const float* __restrict__ X, int64_t N_m, int64_t ldx,
+                                                            int32_t F, int64_t tiles, float* __restrict__ Xt) {
+  const int m = blockIdx.y;
+  const int nchunk = (F + 15) / 16;
+  const int64_t per_worker = tiles * nchunk * 64;            // 16-byte pieces
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= per_worker) return;
+  const int l = (int)(i & 63);
+  const int64_t c = i >> 6;
+  const int t = (int)(c % nchunk);
+  const int64_t row = (c / nchunk) * kRT + (l & 15);
+  const int f = 16 * t + 4 * (l >> 4);
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (row < N_m) {
+    const float* xr = X + ((int64_t)m * N_m + row) * ldx;
+    if (f < F) v.x = xr[f];
+    if (f + 1 < F) v.y = xr[f + 1];
+    if (f + 2 < F) v.z = xr[f + 2];
+    if (f + 3 < F) v.w = xr[f + 3];
+  }
+  reinterpret_cast<float4*>(Xt)[(int64_t)m * per_worker + i] = v;
+}
+
 // ------------------------------------------------------------------ host side
 
 // LDS bytes of the matrix-core softmax kernel (tile slices, partial logits, residuals); 0 if the
@@ -550,6 +601,23 @@ static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block)
   int64_t rpb = (N_m + want - 1) / want;
   *rows_per_block = (int)rpb;
   return (int)((N_m + rpb - 1) / rpb);
+}
+
+size_t tiled_data_bytes(const laq_ctx* ctx) {
+  if (!ctx->X || softmax_mfma_lds(ctx) == 0) return 0;
+  const size_t tiles = (size_t)((ctx->N_m + kRT - 1) / kRT), nchunk = (size_t)((ctx->F + 15) / 16);
+  return (size_t)ctx->M * tiles * nchunk * 256 * sizeof(float);
+}
+
+int tile_data(laq_ctx* ctx, float* Xt) {
+  const int64_t tiles = (ctx->N_m + kRT - 1) / kRT;
+  const int64_t pieces = tiles * ((ctx->F + 15) / 16) * 64;
+  if ((pieces + kThreads - 1) / kThreads > 0x7fffffffll)
+    return set_error(ctx, LAQ_EINVAL, "laq_tile_data: shard too large");
+  hipLaunchKernelGGL(tile_rows_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads), (unsigned)ctx->M),
+                     dim3(kThreads), 0, ctx->stream, ctx->X, ctx->N_m, ctx->ldx, ctx->F, tiles, Xt);
+  LAQ_HIP(ctx, hipGetLastError());
+  return LAQ_OK;
 }
 
 // The matrix-core softmax kernel can take a minibatch's rows straight from the bound data through
@@ -605,15 +673,20 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     const int nchunk = (ctx->F + 15) / 16;
 #define LAQ_SMM(T, NF)                                                                                 \
   do {                                                                                                 \
-    auto kfn = ctx->gather_idx ? softmax_grad_mfma_kernel<T, NF, true> : softmax_grad_mfma_kernel<T, NF, false>; \
+    auto kfn = ctx->gather_idx ? softmax_grad_mfma_kernel<T, NF, kSrcGather>                           \
+               : tiled         ? softmax_grad_mfma_kernel<T, NF, kSrcTiled>                            \
+                               : softmax_grad_mfma_kernel<T, NF, kSrcRows>;                            \
     LAQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                               \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)mfma_lds));      \
-    hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta, ctx->X, ctx->y,   \
+    hipLaunchKernelGGL(kfn, grid, dim3(64 * kSmxWaves), mfma_lds, ctx->stream, theta,                   \
+                       tiled ? ctx->Xtiled : ctx->X, ctx->y,                                            \
                        ctx->N_m, ctx->gather_idx ? ctx->gather_rows : ctx->N_m, ctx->gather_idx,        \
                        ctx->sc.status, ctx->ldx, ctx->F, ctx->C, rpb, part);                            \
   } while (0)
-    // chunks n < nfull exist for every wave and hold no column >= F
-    const int nfull = (ctx->F / 16) / kSmxWaves;
+    // the tiled copy stands for the rows it was made from (a minibatch call binds other rows)
+    const bool tiled = ctx->Xtiled && !ctx->gather_idx && ctx->tiled_for == ctx->X && ctx->tiled_rows == ctx->N_m;
+    // chunks n < nfull exist for every wave and hold no column >= F (the tiled copy is zero there)
+    const int nfull = (tiled ? nchunk : ctx->F / 16) / kSmxWaves;
     if (nchunk <= kSmxWaves) { if (nfull >= 1) LAQ_SMM(1, 1); else LAQ_SMM(1, 0); }
     else if (nchunk <= 2 * kSmxWaves) { if (nfull >= 2) LAQ_SMM(2, 2); else LAQ_SMM(2, 1); }
     else if (nfull >= 4) LAQ_SMM(4, 4);

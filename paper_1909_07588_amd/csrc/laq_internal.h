@@ -79,6 +79,10 @@ struct laq_ctx {
   const float* X = nullptr;
   const int32_t* y = nullptr;
   int64_t N_m = 0, ldx = 0;
+  // Tiled copy of X made by laq_tile_data (caller-owned memory): stands for tiled_for[M][tiled_rows].
+  const float* Xtiled = nullptr;
+  const float* tiled_for = nullptr;
+  int64_t tiled_rows = 0;
   uint8_t* model_ws = nullptr;
   size_t model_ws_bytes = 0;
 
@@ -101,5 +105,7 @@ int set_error(laq_ctx* ctx, int status, const char* fmt, ...);
 size_t model_workspace_bytes(const laq_ctx* ctx, int64_t N_m);
 int worker_grads(laq_ctx* ctx, const float* theta, float* G);
 bool minibatch_reads_in_place(const laq_ctx* ctx);
+size_t tiled_data_bytes(const laq_ctx* ctx);
+int tile_data(laq_ctx* ctx, float* Xt);
 
 }  // namespace laq

@@ -14,6 +14,7 @@ import torch
 
 import laq_synth
 import oracle
+from paper_1909_07588_amd import LaqError
 from gpu_common import (DEV, bits_equal, check_quantize, check_server, make_pair, push_state,
                         to_dev_G)
 
@@ -273,6 +274,93 @@ def test_softmax_gradient_every_chunk_layout_full_batch_and_minibatch(F, C):
     G = Gd[:, :w.p].cpu().numpy()
     assert (np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)).max() <= 1e-5
     assert ctx.laq_get_counters()[2] == 0
+    # the tiled copy of the same rows: same arithmetic in the same order, so the same bits as the
+    # row-major read; the minibatch call still goes through the index list
+    ctx.laq_worker_grads(theta, Gd)
+    torch.cuda.synchronize()
+    G_rows = Gd[:, :w.p].cpu().numpy().copy()
+    if ctx.laq_tiled_data_bytes() == 0:              # (F = 1024 does not fit the matrix-core kernel's LDS)
+        assert F == 1024
+        return
+    ctx.laq_tile_data()
+    Gd.zero_()
+    ctx.laq_worker_grads(theta, Gd)
+    torch.cuda.synchronize()
+    G_tiled = Gd[:, :w.p].cpu().numpy().copy()
+    assert np.array_equal(G_tiled, G_rows)
+    G_full, _ = oracle.grads_all(w.kind, theta_h, X, y, w.dims, w.lam)
+    assert (np.abs(G_tiled - G_full).max(axis=1) / np.abs(G_full).max(axis=1)).max() <= 1e-5
+    ctx.laq_worker_grads_minibatch(theta, torch.from_numpy(idx).to(DEV), Gd)
+    torch.cuda.synchronize()
+    G = Gd[:, :w.p].cpu().numpy()
+    assert (np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)).max() <= 1e-5
+
+
+@pytest.mark.parametrize("N_m", [1, 15, 16, 17, 257])
+def test_tiled_data_small_and_ragged_shards(N_m):
+    """Shards of less than a tile, exactly one tile, and a ragged last tile: the tiled copy pads
+    with zero rows, which must not reach the gradient."""
+    F, C, M = 785, 10, 3
+    w = laq_synth.Workload("t", 2, laq_synth.KIND_SOFTMAX, M, N_m, (F, C), F * C, 3)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    rng = np.random.default_rng(N_m)
+    theta_h = (theta0 + 0.05 * rng.standard_normal(w.p)).astype(np.float32)
+    ctx, st, _ = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta_h)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    assert ctx.laq_tiled_data_bytes() == M * ((N_m + 15) // 16) * ((F + 15) // 16) * 1024
+    ctx.laq_tile_data()
+    theta = torch.from_numpy(theta_h).to(DEV)
+    Gd = ctx.alloc_G()
+    ctx.laq_worker_grads(theta, Gd)
+    torch.cuda.synchronize()
+    G_ref, _ = oracle.grads_all(w.kind, theta_h, X, y, w.dims, w.lam)
+    G = Gd[:, :w.p].cpu().numpy()
+    assert (np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)).max() <= 1e-5
+
+
+def test_tiled_data_is_a_snapshot_and_set_data_drops_it():
+    """After laq_tile_data the gradient kernel reads the copy: a later change of X is seen only after
+    the next laq_tile_data, and binding other data drops the copy."""
+    M, N_m, F, C = 2, 100, 300, 7
+    w = laq_synth.Workload("t", 2, laq_synth.KIND_SOFTMAX, M, N_m, (F, C), F * C, 3)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    theta_h = (theta0 + 0.05 * np.random.default_rng(5).standard_normal(w.p)).astype(np.float32)
+    ctx, st, _ = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta_h)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    Xd, yd = torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV)
+    ctx.laq_set_data(Xd, yd)
+    ctx.laq_tile_data()
+    theta = torch.from_numpy(theta_h).to(DEV)
+    Gd = ctx.alloc_G()
+    G1, _ = oracle.grads_all(w.kind, theta_h, X, y, w.dims, w.lam)
+    X2 = (X * np.float32(0.5)).astype(np.float32)
+    G2, _ = oracle.grads_all(w.kind, theta_h, X2, y, w.dims, w.lam)
+
+    def close(Gref):
+        ctx.laq_worker_grads(theta, Gd)
+        torch.cuda.synchronize()
+        G = Gd[:, :w.p].cpu().numpy()
+        return (np.abs(G - Gref).max(axis=1) / np.abs(Gref).max(axis=1)).max() <= 1e-5
+
+    Xd.copy_(torch.from_numpy(X2).to(DEV))
+    assert close(G1) and not close(G2)              # still the snapshot
+    ctx.laq_tile_data()
+    assert close(G2)
+    Xd.copy_(torch.from_numpy(X).to(DEV))
+    ctx.laq_set_data(Xd, yd)                        # drops the copy: reads X again
+    assert close(G1)
+
+
+def test_tile_data_refused_where_no_kernel_reads_tiles():
+    w = laq_synth.workload(1)                       # binary logistic regression
+    X, y, theta0 = laq_synth.model_inputs(w)
+    ctx, st, theta = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta0)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    assert ctx.laq_tiled_data_bytes() == 0
+    with pytest.raises(LaqError):
+        ctx.laq_tile_data()
 
 
 def test_full_loop_on_the_smallest_workload():

@@ -277,7 +277,8 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
       A.row_off = 0;
       const int yrow = 4 * (wave & 3) + lq;
       A.ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
-      A.lanep = A.base + 4 * lane;                                  // the lane's 16 bytes of chunk 0
+      // the lane's 16 bytes of chunk `wave` (of chunk 0 for a wave past the tile's last chunk)
+      A.lanep = A.base + (256 * (wave < nchunk ? wave : 0) + 4 * lane);
       return A;
     } else {
       A.base = Xm + rb * ldx;
@@ -290,10 +291,9 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   };
   auto gchunk = [&](int n, const TileAddr& A) {
     if constexpr (TILED) {
-      // chunk c lies c KB into the tile; a chunk past the tile's last one reads chunk 0 instead
-      const int c = wave + NW * n;
-      if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 256 * c);
-      return *reinterpret_cast<const float4*>(A.lanep + 256 * (c < nchunk ? c : 0));
+      // chunk wave + 16 n lies 16 KB further per n; one past the tile's last chunk reads the wave's first instead
+      if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 256 * NW * n);
+      return *reinterpret_cast<const float4*>(A.lanep + (wave + NW * n < nchunk ? 256 * NW * n : 0));
     }
     if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 16 * NW * n);
     uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;     // float4 column

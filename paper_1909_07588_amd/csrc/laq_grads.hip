@@ -156,6 +156,15 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kRT = 16;          // rows per tile
 constexpr int kSmxWaves = 16;
 
+// Block barrier that orders LDS accesses only (the waves of the softmax kernel exchange nothing through
+// global memory inside the loop): the general __syncthreads() would also wait for every buffer load in
+// flight, i.e. for the tiles requested two steps ahead.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // value held by lane (i + N) mod 16 of the same 16-lane row (data-parallel primitive, no LDS)
 template <int N>
 __device__ __forceinline__ float row_ror(float x) {
@@ -235,6 +244,11 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   // clamped into the row (rows are padded to ldx, a multiple of 4) and zeroed when consumed.
   const int nf4r = (F + 3) >> 2;
   float4 pre[TMAX];
+  // tiled source: the worker's shard as a buffer resource (its loads return zero outside the shard)
+  typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+  const uint32_t lane_bytes = 16u * (uint32_t)lane;
+  const __amdgpu_buffer_rsrc_t tiled_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(Xm), 0, TILED ? (int)(((N_src + kRT - 1) / kRT) * (int64_t)nchunk * 1024) : 0, 0x00020000);
   int ypre = 0;
   // GATHER: source rows (entries of the index list) of this lane's tile row and of its softmax row,
   // for the tile the next gload will take; requested one gload earlier
@@ -277,8 +291,13 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
       A.row_off = 0;
       const int yrow = 4 * (wave & 3) + lq;
       A.ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
-      // the lane's 16 bytes of chunk `wave` (of chunk 0 for a wave past the tile's last chunk)
-      A.lanep = A.base + (256 * (wave < nchunk ? wave : 0) + 4 * lane);
+      // Byte offset, within the worker's tiled shard, of chunk `wave` of the tile (of chunk 0 for a wave
+      // past the tile's last chunk).  It is the same in all lanes: the loads are buffer loads that take
+      // it from a scalar register and add the lane's constant 16 l themselves, so no vector instruction
+      // computes an address (each one costs this kernel a matrix-instruction slot).
+      A.base = Xm;
+      A.lanep = Xm;
+      A.row_off = (uint32_t)(rb / kRT) * (uint32_t)(nchunk * 1024) + 1024u * (uint32_t)(wave < nchunk ? wave : 0);
       return A;
     } else {
       A.base = Xm + rb * ldx;
@@ -292,8 +311,9 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   auto gchunk = [&](int n, const TileAddr& A) {
     if constexpr (TILED) {
       // chunk wave + 16 n lies 16 KB further per n; one past the tile's last chunk reads the wave's first instead
-      if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 256 * NW * n);
-      return *reinterpret_cast<const float4*>(A.lanep + (wave + NW * n < nchunk ? 256 * NW * n : 0));
+      const uint32_t off = A.row_off + ((n < NFULL || wave + NW * n < nchunk) ? 1024u * NW * n : 0u);
+      const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(tiled_rsrc, (int)lane_bytes, (int)off, 0);
+      return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3]));
     }
     if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 16 * NW * n);
     uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;     // float4 column
@@ -412,22 +432,31 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   ypre = ym[A.ysrc];
   iload(r_begin + kRT);
   A = gaddr(r_begin + kRT);
-  consume(pre, 0, A);
   int ycur = ypre;                                  // labels of this lane's softmax row in the tile of Zp[0]
-  ypre = ym[A.ysrc];
-  iload(r_begin + 2 * kRT);
+  {
+    const int yload = ym[A.ysrc];
+    iload(r_begin + 2 * kRT);
+    consume(pre, 0, A);
+    asm volatile("v_mov_b32 %0, %1" : "=v"(ypre) : "v"(yload));   // (landed before the loop: see below)
+  }
   int buf = 0;
   for (int64_t r0 = r_begin; r0 < r_end; r0 += kRT) {
-    __syncthreads();                                // Zp[buf] complete; Zp[buf ^ 1] and slice buffer buf ^ 1 free
+    lds_barrier();                                  // Zp[buf] complete; Zp[buf ^ 1] and slice buffer buf ^ 1 free
     if (wave < 4) softmax_rows(buf, r0, ycur);      // uniform over the wave
-    __syncthreads();                                // Rs[buf] complete
+    lds_barrier();                                  // Rs[buf] complete
     A = gaddr(r0 + 2 * kRT);
-    const int ynext = ypre;
-    consume(pre, buf ^ 1, A);
-    ypre = ym[A.ysrc];
+    // The label and index requests go out BEFORE the tile's: a wave waits for a load by counting how
+    // many younger ones may still be in flight, so waiting for the youngest request of a step means
+    // waiting for all of them.  And the label is moved to its register at the END of the step it was
+    // requested in (a wait for all but the four tile loads behind it): left in flight across the
+    // loop's back edge it made the compiler wait for every load at the top of the next step, so that
+    // the tile requested two steps ahead had to land within the same step.
+    const int yload = ym[A.ysrc];
     iload(r0 + 3 * kRT);
+    consume(pre, buf ^ 1, A);
     rank_update(buf);
-    ycur = ynext;
+    ycur = ypre;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(ypre) : "v"(yload));
     buf ^= 1;
   }
 

@@ -148,7 +148,8 @@ int laq_set_data(laq_ctx* ctx, const float* X_dev, const int32_t* y_dev, int64_t
  * until laq_tile_data is called again.  laq_worker_grads_minibatch keeps
  * reading X_dev, which must stay alive.  laq_set_model and laq_set_data drop
  * the copy.  laq_tiled_data_bytes returns 0 when the bound model and data
- * have no kernel that reads tiles (then laq_tile_data returns LAQ_EINVAL).
+ * have no kernel that reads tiles, or a worker's shard would reach 4 GB
+ * (then laq_tile_data returns LAQ_EINVAL and the row-major data keep serving).
  */
 size_t laq_tiled_data_bytes(const laq_ctx* ctx);
 int laq_tile_data(laq_ctx* ctx, void* tiled_dev, size_t tiled_bytes);

@@ -635,6 +635,8 @@ static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block)
 size_t tiled_data_bytes(const laq_ctx* ctx) {
   if (!ctx->X || softmax_mfma_lds(ctx) == 0) return 0;
   const size_t tiles = (size_t)((ctx->N_m + kRT - 1) / kRT), nchunk = (size_t)((ctx->F + 15) / 16);
+  // the kernel addresses a worker's tiled shard through a buffer descriptor and 32-bit byte offsets
+  if (tiles * nchunk * 1024 >= ((size_t)1 << 32) - ((size_t)1 << 20)) return 0;
   return (size_t)ctx->M * tiles * nchunk * 256 * sizeof(float);
 }
 

@@ -533,6 +533,8 @@ __global__ __launch_bounds__(kThreads) void binlog_grad_kernel(
 // G[m][i] = (sum over blocks, ascending) part[m][blk][i] / N + (N_m/N) lambda theta[i].
 // Also leaves max_i |G[m][i] - H[m][i]| over this block's coordinates (raw bits)
 // in rprod[m][blockIdx.x]: the quantizer's radius without another pass over G.
+// FLY block partials are in flight at a time (16, or 32 when there are more than 16 of them).
+template <int FLY>
 __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __restrict__ part,
                                                                const float* __restrict__ theta,
                                                                int64_t p, int64_t p_stride, int32_t n_blk,
@@ -546,18 +548,20 @@ __global__ __launch_bounds__(kThreads) void finish_grad_kernel(const float* __re
   if (i < p) {
     const float* pm = part + (int64_t)m * n_blk * p;
     float s = 0.0f;
-    // sixteen block partials in flight (blocks past the last repeat it, unused), added in ascending order
-    for (int k = 0; k < n_blk; k += 16) {
-      float v[16];
+    // FLY block partials in flight (blocks past the last repeat it, unused), added in ascending
+    // order; theta and the stored gradient are requested with the first of them
+    const float th = theta[i], hq = H[(int64_t)m * p_stride + i];
+    for (int k = 0; k < n_blk; k += FLY) {
+      float v[FLY];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = pm[(int64_t)(k + u < n_blk ? k + u : n_blk - 1) * p + i];
+      for (int u = 0; u < FLY; ++u) v[u] = pm[(int64_t)(k + u < n_blk ? k + u : n_blk - 1) * p + i];
 #pragma unroll
-      for (int u = 0; u < 16; ++u)
+      for (int u = 0; u < FLY; ++u)
         if (k + u < n_blk) s += v[u];
     }
-    const float g = fmaf(s, inv_N, reg * theta[i]);
+    const float g = fmaf(s, inv_N, reg * th);
     G[(int64_t)m * p_stride + i] = g;
-    mx = __float_as_uint(g - H[(int64_t)m * p_stride + i]) & 0x7fffffffu;
+    mx = __float_as_uint(g - hq) & 0x7fffffffu;
   }
   __shared__ uint32_t sm[kWaves];
 #pragma unroll
@@ -749,8 +753,12 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   const size_t part_bytes = ((size_t)ctx->M * nb * ctx->p * sizeof(float) + 255) & ~(size_t)255;
   ctx->rprod = reinterpret_cast<uint32_t*>(ctx->model_ws + part_bytes);
   ctx->rprod_stride = ctx->rprod_count = (int32_t)fgrid.x;
-  hipLaunchKernelGGL(finish_grad_kernel, fgrid, dim3(kThreads), 0, ctx->stream, part, theta, ctx->p,
-                     ctx->p_stride, nb, inv_N, reg, G, ctx->H, ctx->rprod);
+  if (nb > 16)
+    hipLaunchKernelGGL(finish_grad_kernel<32>, fgrid, dim3(kThreads), 0, ctx->stream, part, theta, ctx->p,
+                       ctx->p_stride, nb, inv_N, reg, G, ctx->H, ctx->rprod);
+  else
+    hipLaunchKernelGGL(finish_grad_kernel<16>, fgrid, dim3(kThreads), 0, ctx->stream, part, theta, ctx->p,
+                       ctx->p_stride, nb, inv_N, reg, G, ctx->H, ctx->rprod);
   LAQ_HIP(ctx, hipGetLastError());
   return LAQ_OK;
 }

@@ -237,6 +237,39 @@ def pmc_probe():
     print("pmc probe done", flush=True)
 
 
+def _run_fixed_iterations(w, Xd, yd, theta0, b, force, iters):
+    """iters whole iterations with b-bit (or exact) messages, skip rule on or off; the counters."""
+    import torch
+    import paper_1909_07588_amd as laq
+    dev = "cuda:0"
+    ctx = laq.Laq(w.M, w.p, b, w.D, w.xi, w.t_bar, w.alpha, device=dev)
+    if force:
+        ctx.laq_set_mode(laq.MODE_FORCE_UPLOAD)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(Xd, yd)
+    if ctx.laq_tiled_data_bytes() > 0:
+        ctx.laq_tile_data()
+    theta = torch.from_numpy(theta0.copy()).to(dev)
+    G = ctx.alloc_G()
+    codes, R, up = ctx.alloc_messages()
+    e0, e1 = _events(torch, 2)
+    e0.record()
+    for _ in range(iters):
+        ctx.laq_worker_grads(theta, G)
+        ctx.laq_quantize_skip(G, codes, R, up)
+        ctx.laq_server_step(codes, R, up, theta)
+    e1.record()
+    torch.cuda.synchronize()
+    uploads, bits, status = ctx.laq_get_counters()
+    row = {"b": int(b), "alpha": w.alpha, "status": int(status), "iterations": iters, "uploads": int(uploads.sum()),
+           "uploads_per_worker": [int(u) for u in uploads],
+           "upload_fraction": round(float(uploads.sum()) / (iters * w.M), 4),
+           "bits": int(bits), "last_dtheta2": float(ctx.state()["dtheta2"][0].item()),
+           "ms_per_iteration": round(e0.elapsed_time(e1) / iters, 5)}
+    ctx.close()
+    return row
+
+
 def modes_table(iters=500):
     """Table-2-style rows on the headline shapes (synthetic data): the same kernels run as GD
     (exact messages, every worker uploads), QGD (Algorithm 1: b-bit messages, every worker
@@ -252,30 +285,39 @@ def modes_table(iters=500):
     rows = []
     for name, b, force in (("GD", laq.B_EXACT, True), ("QGD", w.b, True), ("LAG", laq.B_EXACT, False),
                            ("LAQ", w.b, False)):
-        ctx = laq.Laq(w.M, w.p, b, w.D, w.xi, w.t_bar, w.alpha, device=dev)
-        if force:
-            ctx.laq_set_mode(laq.MODE_FORCE_UPLOAD)
-        ctx.laq_set_model(w.kind, w.dims, w.lam)
-        ctx.laq_set_data(Xd, yd)
-        ctx.laq_tile_data()
-        theta = torch.from_numpy(theta0.copy()).to(dev)
-        G = ctx.alloc_G()
-        codes, R, up = ctx.alloc_messages()
-        e0, e1 = _events(torch, 2)
-        e0.record()
-        for _ in range(iters):
-            ctx.laq_worker_grads(theta, G)
-            ctx.laq_quantize_skip(G, codes, R, up)
-            ctx.laq_server_step(codes, R, up, theta)
-        e1.record()
-        torch.cuda.synchronize()
-        uploads, bits, status = ctx.laq_get_counters()
-        assert status == 0
-        rows.append({"mode": name, "b": int(b), "iterations": iters, "uploads": int(uploads.sum()),
-                     "bits": int(bits), "last_dtheta2": float(ctx.state()["dtheta2"][0].item()),
-                     "ms_per_iteration": round(e0.elapsed_time(e1) / iters, 5)})
-        ctx.close()
+        rows.append(dict({"mode": name}, **_run_fixed_iterations(w, Xd, yd, theta0, b, force, iters)))
     print(json.dumps({"workload": w.name, "alpha": w.alpha, "table": rows}), flush=True)
+
+
+def sweeps_table(iters=500):
+    """The two sweeps announced at the end of Sec. 4, on the smallest workload and the headline shapes (synthetic data):
+    LAQ over the number of bits per coordinate, and LAQ beside GD over the level of heterogeneity
+    between the workers' shards (laq_synth.heterogeneous); uploads, bits and the final
+    alpha^2 ||nabla||^2 after a fixed number of iterations."""
+    import torch
+    import laq_synth
+    import paper_1909_07588_amd as laq
+    dev = "cuda:0"
+    out = []
+    # planted labels and the headline shapes, each at its own step size and at ten times that (the
+    # larger steps move the gradients enough for rule (7a) to fire between the forced uploads)
+    for cfg, scale_alpha in ((1, 1.0), (1, 10.0), (2, 1.0), (2, 10.0)):
+        w = laq_synth.workload(cfg)
+        w.alpha = w.alpha * scale_alpha
+        X, y, theta0 = laq_synth.model_inputs(w)
+        Xd, yd = torch.from_numpy(X).to(dev), torch.from_numpy(y).to(dev)
+        bits_rows = [dict({"mode": "LAQ"}, **_run_fixed_iterations(w, Xd, yd, theta0, b, False, iters))
+                     for b in (1, 2, 3, 4, 6, 8, 12, 16)]
+        het_rows = []
+        for level in (0.0, 0.25, 0.5, 1.0):
+            Xh, yh = laq_synth.heterogeneous(w, X, y, level)
+            Xd, yd = torch.from_numpy(Xh).to(dev), torch.from_numpy(yh).to(dev)
+            for name, b, force in (("GD", laq.B_EXACT, True), ("LAQ", w.b, False)):
+                het_rows.append(dict({"mode": name, "level": level},
+                                     **_run_fixed_iterations(w, Xd, yd, theta0, b, force, iters)))
+        out.append({"workload": w.name, "alpha": w.alpha, "bits_sweep": bits_rows,
+                    "heterogeneity_sweep": het_rows})
+    print(json.dumps({"sweeps": out}), flush=True)
 
 
 def cpu_baseline(w, budget_s=12.0, max_iters=50):
@@ -312,6 +354,8 @@ def main():
     ap.add_argument("--pmc-probe", action="store_true", help="short run for rocprofv3 --pmc (no timing)")
     ap.add_argument("--modes-table", action="store_true",
                     help="GD / QGD / LAG / LAQ on the headline shapes: uploads and bits after --steps iterations")
+    ap.add_argument("--sweeps-table", action="store_true",
+                    help="LAQ over b, and LAQ beside GD over the heterogeneity level, on the headline shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all M workers are simulated on one MI355X); "
@@ -330,6 +374,9 @@ def main():
         return
     if args.modes_table:
         modes_table(args.steps)
+        return
+    if args.sweeps_table:
+        sweeps_table(args.steps)
         return
     traffic = _traffic_table()
 

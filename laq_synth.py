@@ -122,6 +122,30 @@ def model_inputs(w):
     raise ValueError("workload has no model")
 
 
+def heterogeneous(w, X, y, level):
+    """Copies of a model workload's (X, y) with the shards made unlike each other; level in [0, 1],
+    0 returns the inputs unchanged.  Worker m's features (not a bias column) are scaled by
+    10^(-level * m / (M - 1)), so the workers' smoothness constants spread over 10^(2 level); and each
+    label is, with probability level, replaced by the class m mod C (label skew).  Stands in for the
+    heterogeneity sweep announced at the end of Sec. 4, whose recipe the paper does not print."""
+    if not 0.0 <= level <= 1.0:
+        raise ValueError("level must lie in [0, 1]")
+    if level == 0.0:
+        return X, y
+    rng = _rng(w.cfg, stream=500)
+    M = w.M
+    F = w.dims[0] - (1 if w.kind == KIND_SOFTMAX else 0)      # the softmax workload's last column is the bias
+    Xh, yh = X.copy(), y.copy()
+    if w.kind != KIND_BINLOG:
+        Cn = w.dims[-1]
+        swap = rng.random(y.shape) < level
+    for m in range(M):
+        Xh[m, :, :F] *= np.float32(10.0 ** (-level * m / max(M - 1, 1)))
+        if w.kind != KIND_BINLOG:
+            yh[m][swap[m]] = m % Cn
+    return Xh, yh
+
+
 def minibatch_indices(w, B, iteration):
     """Sample indices idx[M][B] (int32, into each worker's own shard, without repeats inside
     a batch) for one stochastic iteration; a function of (workload, B, iteration) only."""

@@ -399,6 +399,12 @@ def main():
         ws.alpha = 0.008
         r, _ = run_model_workload(ws, 500, 10, phase_steps=100, minibatch=500)
         workloads.append(r)
+        # ... and on the small network (Sec. 4: minibatch 500, alpha = 0.008, b = 8)
+        ws = laq_synth.workload(3)
+        ws.alpha = 0.008
+        r, _ = run_model_workload(ws, 300, 10, phase_steps=100, minibatch=500)
+        workloads.append(r)
+        torch.cuda.empty_cache()
         for b in (2, 4, 8):
             r, (alg_q, tq, alg_s, ts) = run_stress(b, 50, 3)
             name = r["workload"]

@@ -433,14 +433,21 @@ def test_full_loop_on_a_scaled_network_workload():
 def test_full_size_stress_shape_all_workers():
     """The bandwidth-stress workload at its full size (M = 64, p = 2^24, b = 4), in the launch
     configuration bench.py times: radii, both integer sums, both sides of (7a) and the masks
-    of all 64 workers, the packed codes of 6 sampled workers, and one whole server step."""
+    of all 64 workers, the packed codes of 6 sampled workers, and one whole server step; the
+    third iteration with the radius handed over by the caller (a single pass)."""
     w = laq_synth.workload(4)
     M, p, b = w.M, w.p, 4
     ctx, st, theta = make_pair(M, p, b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha)
     Gd, s, gen = laq_synth.device_gradients(M, p, ctx.p_stride, DEV)
     codes, R, up = ctx.alloc_messages()
-    for it in range(2):
+    rmax = torch.zeros((M, 1), dtype=torch.float32, device=DEV)
+    for it in range(3):
         G = Gd[:, :p].cpu().numpy()
+        if it == 2:           # the fourth stress line: the producer of the gradients hands the radius over
+            Hd = ctx.state()["H"]
+            for m in range(M):
+                rmax[m, 0] = (Gd[m] - Hd[m]).abs_().max()
+            ctx.laq_radius_handover(Gd, rmax.view(torch.int32))
         ctx.laq_quantize_skip(Gd, codes, R, up)
         torch.cuda.synchronize()
         sview = ctx.state()

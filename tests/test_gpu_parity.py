@@ -430,18 +430,19 @@ def test_full_loop_on_a_scaled_network_workload():
         push_state(ctx, st)
 
 
-def test_full_size_stress_shape_all_workers():
-    """The bandwidth-stress workload at its full size (M = 64, p = 2^24, b = 4), in the launch
+@pytest.mark.parametrize("b,iters", [(4, 3), (2, 1), (8, 1)])
+def test_full_size_stress_shape_all_workers(b, iters):
+    """The bandwidth-stress workload at its full size (M = 64, p = 2^24, b = 4, 2, 8), in the launch
     configuration bench.py times: radii, both integer sums, both sides of (7a) and the masks
     of all 64 workers, the packed codes of 6 sampled workers, and one whole server step; the
-    third iteration with the radius handed over by the caller (a single pass)."""
+    third iteration (b = 4) with the radius handed over by the caller (a single pass)."""
     w = laq_synth.workload(4)
-    M, p, b = w.M, w.p, 4
+    M, p = w.M, w.p
     ctx, st, theta = make_pair(M, p, b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha)
     Gd, s, gen = laq_synth.device_gradients(M, p, ctx.p_stride, DEV)
     codes, R, up = ctx.alloc_messages()
     rmax = torch.zeros((M, 1), dtype=torch.float32, device=DEV)
-    for it in range(3):
+    for it in range(iters):
         G = Gd[:, :p].cpu().numpy()
         if it == 2:           # the fourth stress line: the producer of the gradients hands the radius over
             Hd = ctx.state()["H"]

@@ -320,7 +320,7 @@ def sweeps_table(iters=500):
     print(json.dumps({"sweeps": out}), flush=True)
 
 
-def cpu_baseline(w, budget_s=12.0, max_iters=50):
+def cpu_baseline(w, budget_s=12.0, max_iters=1000):
     """The oracle, as it stands, on the host cores: whole LAQ iterations of the same workload."""
     import numpy as np
     import laq_synth

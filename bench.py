@@ -387,7 +387,7 @@ def main():
     workloads = [dict(res, rooflines=roofs)]
 
     if not args.primary_only:
-        for cfg, k, wu in ((3, 200, 10), (5, 6, 2)):
+        for cfg, k, wu in ((1, 200, 10), (3, 200, 10), (5, 6, 2)):
             if cfg == args.workload:
                 continue
             wk = laq_synth.workload(cfg)

@@ -959,7 +959,7 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
 
 struct Layout {
   size_t H, nabla, scalars, total;
-  size_t Rpart, Spart, Npart, Rfin, ticket, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
+  size_t Rpart, Spart, Npart, Rfin, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
       dtheta2, xi, srv_part, scalars_end;
 };
 
@@ -1012,7 +1012,6 @@ static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   l.Spart = take((size_t)M * slots * 8);
   l.Npart = take((size_t)M * slots * 8);
   l.Rfin = take((size_t)M * 4);
-  l.ticket = take((size_t)M * 4);
   l.Sq = take((size_t)M * 8);
   l.E2 = take((size_t)M * 8);
   l.lhs = take((size_t)M * 8);
@@ -1174,7 +1173,6 @@ int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const 
   s.Spart = (unsigned long long*)(w + l.Spart);
   s.Npart = (unsigned long long*)(w + l.Npart);
   s.Rfin = (uint32_t*)(w + l.Rfin);
-  s.ticket = (uint32_t*)(w + l.ticket);
   s.Sq = (long long*)(w + l.Sq);
   s.E2 = (double*)(w + l.E2);
   s.lhs = (double*)(w + l.lhs);

@@ -18,7 +18,6 @@ struct DeviceScalars {
   unsigned long long* Spart;    // [M][slots] block sums of (2q-L)^2
   unsigned long long* Npart;    // [M][slots] block sums of the integer error squares
   uint32_t* Rfin;               // [M] radius of the current call (raw bits)
-  uint32_t* ticket;             // [M] (unused: kept so that the workspace layout stays as it was)
   long long* Sq;                // [M] stash
   double* E2;                   // [M] stash
   double* lhs;                  // [M]

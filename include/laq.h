@@ -159,8 +159,12 @@ int laq_tile_data(laq_ctx* ctx, void* tiled_dev, size_t tiled_bytes);
  * all M workers (fp32 arithmetic; row stride laq_p_stride(p)).
  * theta_dev[p] is read only.  Needs laq_set_model and laq_set_data.
  * The kernels that write G also leave max |g - h| per block, so a following
- * laq_quantize_skip on the same G_dev, with the state untouched in between,
- * skips its radius pass (one read of G and of the stored gradients less).
+ * laq_quantize_skip on the same G_dev skips its radius pass (one read of G and
+ * of the stored gradients less), provided neither the state nor the contents
+ * of G_dev change in between.  A caller that edits G_dev in place (clipping,
+ * added noise) must withdraw the hand-over with laq_radius_handover(ctx, NULL,
+ * NULL, 0) before it calls laq_quantize_skip; the library cannot see such an
+ * edit and would quantize with the radius of the gradients as it wrote them.
  */
 int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev);
 
@@ -209,13 +213,19 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev,
  * maximum on the way, as laq_worker_grads does): declares that
  * rmax_dev[m * count + i], i < count, hold the raw bits of max |g_j - h_j| over
  * the i-th part of any partition of worker m's coordinates (h = the stored
- * quantized gradients, laq_state_view.H_dev).  The next laq_quantize_skip on
- * the same G_dev then skips its radius pass, provided the state has not
- * changed in between (laq_server_step, laq_set_state, laq_get_state and
- * laq_reset withdraw the declaration).  rmax_dev (device, caller-owned) is read
- * when laq_quantize_skip runs.  The values are trusted: if their maximum is
- * not ||g_m - h_m||_inf the codes are those of eq. 5 for that other radius,
- * clamped to [0, L].  count >= 1.
+ * quantized gradients, laq_state_view.H_dev).  Every laq_quantize_skip on the
+ * same G_dev then skips its radius pass until the declaration is withdrawn:
+ * by laq_server_step, laq_get_state, laq_reset, laq_set_model,
+ * laq_worker_grads (which leaves its own), or by this call with count = 0
+ * (G_dev and rmax_dev are then ignored).  A laq_quantize_skip on another G_dev
+ * in between runs its own radius pass and leaves the declaration intact.  The
+ * caller must withdraw it before it changes the contents of G_dev.
+ * rmax_dev (device, caller-owned): with count <= 64 it is read by each such
+ * laq_quantize_skip and must stay alive and unchanged until then; with count >
+ * 64 it is read by a kernel this call enqueues on the stream (the maxima are
+ * combined once into the workspace) and may be reused after that.  The values
+ * are trusted: if their maximum is not ||g_m - h_m||_inf the codes are those of
+ * eq. 5 for that other radius, clamped to [0, L].  count >= 0.
  */
 int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_dev, int32_t count);
 

@@ -252,7 +252,11 @@ class Laq:
 
     def laq_radius_handover(self, G, rmax):
         """rmax: uint32 (or int32) device tensor [M][count], raw bits of block maxima of |g - h|;
-        the caller keeps it alive until the next laq_quantize_skip has run."""
+        the caller keeps it alive until the next laq_quantize_skip has run.  rmax = None withdraws
+        a hand-over (count = 0)."""
+        if rmax is None:
+            self._chk(self.L.laq_radius_handover(self.h, None, None, 0))
+            return
         assert rmax.dim() == 2 and rmax.shape[0] == self.M and rmax.is_contiguous() and rmax.element_size() == 4
         self._chk(self.L.laq_radius_handover(self.h, C.c_void_p(G.data_ptr()), C.c_void_p(rmax.data_ptr()),
                                              int(rmax.shape[1])))

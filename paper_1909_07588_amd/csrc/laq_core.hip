@@ -216,9 +216,10 @@ struct QuantArgs {
   int64_t p, p_stride, w_stride;
   int32_t M, D, t_bar, eps_K, slots, U;
   int32_t fused_decide;   // 1: one block per worker, which applies the skip rule itself
-  // radius source: either the finished value Rfin[m] (rcount == 0) or at most 64
+  // radius source: either the finished value rfin[m] (rcount == 0) or at most 64
   // block maxima rsrc[m * rstride + i], i < rcount, combined on the fly
   const uint32_t* rsrc;
+  const uint32_t* rfin;
   int32_t rstride, rcount;
   float alpha;
   uint32_t mode;
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void codes_kernel(Q
       const int lane = threadIdx.x & 63;
       rbits = a.rsrc[(int64_t)m * a.rstride + (lane < a.rcount ? lane : 0)];   // (duplicates do not change a maximum)
     } else {
-      rbits = a.sc.Rfin[m];
+      rbits = a.rfin[m];
     }
     // SOLO: everything the block will read is requested here, before the first wait: the lane's
     // group of g and h, the ragged tail, the terms of the skip rule.  The loads are
@@ -496,7 +497,7 @@ __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t
   if (a.rcount > 0) {
     if ((int)threadIdx.x < a.rcount) rb = a.rsrc[(int64_t)m * a.rstride + threadIdx.x];
   } else if (threadIdx.x == 0) {
-    rb = a.sc.Rfin[m];
+    rb = a.rfin[m];
   }
   s64 = wave_sum_u64(s64);
   n64 = wave_sum_u64(n64);
@@ -650,6 +651,7 @@ __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks,
                                               const double* own_total);
 
 constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
+constexpr int kServerList = 4096;   // workers per round of the server step (12 bytes of LDS each)
 
 // eq. 4: nabla^k = nabla^{k-1} + sum_{m in M^k} deltaQ_m, theta^{k+1} = theta^k - alpha nabla^k,
 // with Q_m(theta_hat_m) += deltaQ_m for the uploading workers (Alg. 2, upload branch).
@@ -666,9 +668,10 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void server_kernel(
   constexpr int JN = SOLO ? 1 : kServerJ;
   constexpr uint32_t L = B >= 32 ? 0xffffffffu : (1u << (B & 31)) - 1u;
   extern __shared__ unsigned char smem_raw[];
-  int32_t* list = reinterpret_cast<int32_t*>(smem_raw);           // [M] uploading workers, ascending
-  float* Rm = reinterpret_cast<float*>(list + a.M);               // [M]
-  float* stepm = Rm + a.M;                                        // [M]
+  const int lcap = a.M < kServerList ? a.M : kServerList;
+  int32_t* list = reinterpret_cast<int32_t*>(smem_raw);           // [lcap] uploading workers of a round, ascending
+  float* Rm = reinterpret_cast<float*>(list + lcap);              // [lcap]
+  float* stepm = Rm + lcap;                                       // [lcap]
   __shared__ int n_up_s;
 
   const int64_t nfull = a.p / kGroup;
@@ -695,80 +698,129 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void server_kernel(
     }
   }
 
-  // ascending list of workers whose message carries a non-zero innovation
-  // (order-preserving compaction: wavefront ballots + prefix counts)
+  // Uploading workers are taken in ascending rounds of at most kServerList workers, so the LDS need
+  // does not grow with M; inside a round: the ascending list of workers whose message carries a
+  // non-zero innovation (order-preserving compaction: wavefront ballots + prefix counts).
   __shared__ int wave_cnt[NT / 64];
-  if (threadIdx.x == 0) n_up_s = 0;
-  for (int base = 0; base < a.M; base += NT) {
-    const int m = base + threadIdx.x;
-    bool on = false;
-    if (m < a.M) {
-      const float R = a.R_in[m];
-      const QuantConst c = quant_const<B>(__float_as_uint(R));
-      Rm[m] = R;
-      on = a.upload[m] && (B == kExact || !c.zero);   // the exact message is stored even if it repeats h
-      stepm[m] = on ? c.step : -1.0f;
-    }
-    const unsigned long long bal = __ballot(on);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) wave_cnt[wave] = __popcll(bal);
-    __syncthreads();
-    int before = n_up_s;
-    for (int wv = 0; wv < wave; ++wv) before += wave_cnt[wv];
-    if (on) list[before + __popcll(bal & ((1ull << lane) - 1ull))] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int tot = 0;
-#pragma unroll
-      for (int wv = 0; wv < NT / 64; ++wv) tot += wave_cnt[wv];
-      n_up_s += tot;
-    }
-    __syncthreads();
-  }
-  const int n_up = n_up_s;
-
   float acc[JN][kGroup];
 #pragma unroll
   for (int j = 0; j < JN; ++j)
 #pragma unroll
     for (int i = 0; i < kGroup; ++i) acc[j][i] = 0.0f;
-  for (int k = 0; k < n_up; ++k) {
-    const int m = list[k];
-    const float R = Rm[m], step = stepm[m];
-    const uint8_t* crow = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
-    float* hrow = a.H + (int64_t)m * a.p_stride;
+  float acc_tail[kGroup - 1];                      // wavefront 0 of block 0: the p % 8 last coordinates
 #pragma unroll
-    for (int j = 0; j < JN; ++j) {
-      const int64_t grp = grp0 + j * span;
-      if (j < a.J && grp < nfull) {
-        float4* hp = reinterpret_cast<float4*>(hrow + grp * kGroup);
-        const float4 h0 = hp[0], h1 = hp[1];
-        float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-        if constexpr (B == kExact) {
-          const float4* cp = reinterpret_cast<const float4*>(crow + grp * (int64_t)(kGroup * 4));
-          const float4 g0 = cp[0], g1 = cp[1];
-          const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+  for (int k = 0; k < kGroup - 1; ++k) acc_tail[k] = 0.0f;
+
+  for (int m0 = 0; m0 < a.M; m0 += kServerList) {
+    const int mcnt = a.M - m0 < kServerList ? a.M - m0 : kServerList;
+    if (threadIdx.x == 0) n_up_s = 0;
+    for (int base = 0; base < mcnt; base += NT) {
+      const int ml = base + threadIdx.x;             // index inside the round
+      bool on = false;
+      if (ml < mcnt) {
+        const float R = a.R_in[m0 + ml];
+        const QuantConst c = quant_const<B>(__float_as_uint(R));
+        Rm[ml] = R;
+        on = a.upload[m0 + ml] && (B == kExact || !c.zero);   // the exact message is stored even if it repeats h
+        stepm[ml] = on ? c.step : -1.0f;
+      }
+      const unsigned long long bal = __ballot(on);
+      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+      if (lane == 0) wave_cnt[wave] = __popcll(bal);
+      __syncthreads();
+      int before = n_up_s;
+      for (int wv = 0; wv < wave; ++wv) before += wave_cnt[wv];
+      if (on) list[before + __popcll(bal & ((1ull << lane) - 1ull))] = ml;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int tot = 0;
 #pragma unroll
-          for (int i = 0; i < kGroup; ++i) {
-            const float dq = gv[i] - hv[i];
-            hv[i] = gv[i];
-            acc[j][i] = acc[j][i] + dq;
+        for (int wv = 0; wv < NT / 64; ++wv) tot += wave_cnt[wv];
+        n_up_s += tot;
+      }
+      __syncthreads();
+    }
+    const int n_up = n_up_s;
+
+    for (int k = 0; k < n_up; ++k) {
+      const int ml = list[k];
+      const int m = m0 + ml;
+      const float R = Rm[ml], step = stepm[ml];
+      const uint8_t* crow = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+      float* hrow = a.H + (int64_t)m * a.p_stride;
+#pragma unroll
+      for (int j = 0; j < JN; ++j) {
+        const int64_t grp = grp0 + j * span;
+        if (j < a.J && grp < nfull) {
+          float4* hp = reinterpret_cast<float4*>(hrow + grp * kGroup);
+          const float4 h0 = hp[0], h1 = hp[1];
+          float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+          if constexpr (B == kExact) {
+            const float4* cp = reinterpret_cast<const float4*>(crow + grp * (int64_t)(kGroup * 4));
+            const float4 g0 = cp[0], g1 = cp[1];
+            const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) {
+              const float dq = gv[i] - hv[i];
+              hv[i] = gv[i];
+              acc[j][i] = acc[j][i] + dq;
+            }
+          } else {
+            const unsigned __int128 v = load_group<B>(crow + grp * B);
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) {
+              const uint32_t q = (uint32_t)(v >> (i * B)) & L;
+              float dq = (float)q * step;
+              dq = dq - R;
+              hv[i] = hv[i] + dq;
+              acc[j][i] = acc[j][i] + dq;
+            }
           }
-        } else {
-          const unsigned __int128 v = load_group<B>(crow + grp * B);
-#pragma unroll
-          for (int i = 0; i < kGroup; ++i) {
-            const uint32_t q = (uint32_t)(v >> (i * B)) & L;
-            float dq = (float)q * step;
-            dq = dq - R;
-            hv[i] = hv[i] + dq;
-            acc[j][i] = acc[j][i] + dq;
-          }
+          hp[0] = make_float4(hv[0], hv[1], hv[2], hv[3]);
+          hp[1] = make_float4(hv[4], hv[5], hv[6], hv[7]);
         }
-        hp[0] = make_float4(hv[0], hv[1], hv[2], hv[3]);
-        hp[1] = make_float4(hv[4], hv[5], hv[6], hv[7]);
       }
     }
+    // The p % 8 coordinates after the last whole group: wavefront 0 of block 0.  Lane l takes the
+    // l-th uploader of a group of 64 (all their loads are in flight together; one thread walking the
+    // uploaders would pay two memory latencies for each), then the contributions are added in
+    // ascending worker order.
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+      const int lane = threadIdx.x;
+#pragma unroll
+      for (int kt = 0; kt < kGroup - 1; ++kt) {
+        const int64_t i = nfull * kGroup + kt;
+        if (i >= a.p) break;
+        float acc1 = acc_tail[kt];
+        for (int k0 = 0; k0 < n_up; k0 += 64) {
+          const int k = k0 + lane;
+          float dq = 0.0f;
+          if (k < n_up) {
+            const int ml = list[k];
+            const int m = m0 + ml;
+            const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
+            float* hp = a.H + (int64_t)m * a.p_stride + i;
+            if constexpr (B == kExact) {
+              const float gval = reinterpret_cast<const float*>(row)[i];
+              dq = gval - *hp;
+              *hp = gval;
+            } else {
+              const int64_t bit = i * B;
+              uint32_t q = 0;
+              for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
+              dq = (float)q * stepm[ml];
+              dq = dq - Rm[ml];
+              *hp = *hp + dq;
+            }
+          }
+          const int cnt = n_up - k0 < 64 ? n_up - k0 : 64;
+          for (int l = 0; l < cnt; ++l)
+            acc1 = acc1 + __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dq), l));
+        }
+        acc_tail[kt] = acc1;
+      }
+    }
+    __syncthreads();                                 // the next round rewrites the list
   }
 
   double n2 = 0.0;
@@ -800,53 +852,23 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void server_kernel(
       tp4[1] = make_float4(tv[4], tv[5], tv[6], tv[7]);
     }
   }
-  // The p % 8 coordinates after the last whole group: wavefront 0 of block 0.  Lane l takes the
-  // l-th uploader of a round of 64 (all their loads are in flight together; one thread walking the
-  // uploaders would pay two memory latencies for each), then the contributions are added in
-  // ascending worker order.
-  if (blockIdx.x == 0 && threadIdx.x < 64) {
-    const int lane = threadIdx.x;
-    for (int64_t i = nfull * kGroup; i < a.p; ++i) {
-      float acc1 = 0.0f;
-      for (int k0 = 0; k0 < n_up; k0 += 64) {
-        const int k = k0 + lane;
-        float dq = 0.0f;
-        if (k < n_up) {
-          const int m = list[k];
-          const uint8_t* row = reinterpret_cast<const uint8_t*>(a.codes + (int64_t)m * a.w_stride);
-          float* hp = a.H + (int64_t)m * a.p_stride + i;
-          if constexpr (B == kExact) {
-            const float gval = reinterpret_cast<const float*>(row)[i];
-            dq = gval - *hp;
-            *hp = gval;
-          } else {
-            const int64_t bit = i * B;
-            uint32_t q = 0;
-            for (int t = 0; t < B; ++t) q |= (uint32_t)((row[(bit + t) >> 3] >> ((bit + t) & 7)) & 1u) << t;
-            dq = (float)q * stepm[m];
-            dq = dq - Rm[m];
-            *hp = *hp + dq;
-          }
-        }
-        const int cnt = n_up - k0 < 64 ? n_up - k0 : 64;
-        for (int l = 0; l < cnt; ++l)
-          acc1 = acc1 + __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dq), l));
-      }
-      if (lane == 0) {
-        float nb_old = 0.0f, th_old = 0.0f;
-        if constexpr (SOLO) {                          // fetched at the start of the kernel
+  // the p % 8 last coordinates: their sums over the uploaders were formed above (wavefront 0 of block 0)
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
 #pragma unroll
-          for (int k = 0; k < kGroup - 1; ++k)
-            if (i == nfull * kGroup + k) { nb_old = tn[k]; th_old = tt[k]; }
-        } else {
-          nb_old = a.nabla[i]; th_old = a.theta[i];
-        }
-        const float nb = nb_old + acc1;
-        a.nabla[i] = nb;
-        const float st = a.alpha * nb;
-        a.theta[i] = th_old - st;
-        n2 = fma((double)nb, (double)nb, n2);
+    for (int kt = 0; kt < kGroup - 1; ++kt) {
+      const int64_t i = nfull * kGroup + kt;
+      if (i >= a.p) break;
+      float nb_old, th_old;
+      if constexpr (SOLO) {                          // fetched at the start of the kernel
+        nb_old = tn[kt]; th_old = tt[kt];
+      } else {
+        nb_old = a.nabla[i]; th_old = a.theta[i];
       }
+      const float nb = nb_old + acc_tail[kt];
+      a.nabla[i] = nb;
+      const float st = a.alpha * nb;
+      a.theta[i] = th_old - st;
+      n2 = fma((double)nb, (double)nb, n2);
     }
   }
 
@@ -959,7 +981,7 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, int n) {
 
 struct Layout {
   size_t H, nabla, scalars, total;
-  size_t Rpart, Spart, Npart, Rfin, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
+  size_t Rpart, Spart, Npart, Rfin, Rhand, Sq, E2, lhs, rhs, Ehat2, t, uploads, bits, status, srv_ticket,
       dtheta2, xi, srv_part, scalars_end;
 };
 
@@ -983,13 +1005,12 @@ static int32_t partial_slots(int32_t M) {
   return s < 32 ? 32 : s;
 }
 
-// Grid of the two streaming passes: Gx blocks per worker, U tiles per block.
-static Sweep make_sweep(int64_t p, int32_t M) {
+// Grid of the two streaming passes: Gx blocks per worker (at most max_gx), U tiles per block.
+static Sweep make_sweep(int64_t p, int64_t max_gx) {
   Sweep sw;
   sw.nfull = p / kGroup;
   sw.T = (sw.nfull + kThreads - 1) / kThreads;
   if (sw.T < 1) sw.T = 1;
-  const int64_t max_gx = partial_slots(M);
   sw.U = (int32_t)((sw.T + max_gx - 1) / max_gx);
   if (sw.T <= 4) sw.U = (int32_t)sw.T;   // small problems: one block per worker finishes its own skip test
   sw.Gx = (int32_t)((sw.T + sw.U - 1) / sw.U);
@@ -997,7 +1018,7 @@ static Sweep make_sweep(int64_t p, int32_t M) {
 }
 
 // Slots actually used (and allocated) per worker.
-static int32_t used_slots(int64_t p, int32_t M) { return make_sweep(p, M).Gx; }
+static int32_t used_slots(int64_t p, int32_t M) { return make_sweep(p, partial_slots(M)).Gx; }
 
 static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   Layout l{};
@@ -1012,6 +1033,7 @@ static Layout make_layout(int32_t M, int64_t p, int32_t D) {
   l.Spart = take((size_t)M * slots * 8);
   l.Npart = take((size_t)M * slots * 8);
   l.Rfin = take((size_t)M * 4);
+  l.Rhand = take((size_t)M * 4);
   l.Sq = take((size_t)M * 8);
   l.E2 = take((size_t)M * 8);
   l.lhs = take((size_t)M * 8);
@@ -1173,6 +1195,7 @@ int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const 
   s.Spart = (unsigned long long*)(w + l.Spart);
   s.Npart = (unsigned long long*)(w + l.Npart);
   s.Rfin = (uint32_t*)(w + l.Rfin);
+  s.Rhand = (uint32_t*)(w + l.Rhand);
   s.Sq = (long long*)(w + l.Sq);
   s.E2 = (double*)(w + l.E2);
   s.lhs = (double*)(w + l.lhs);
@@ -1218,21 +1241,20 @@ int laq_set_mode(laq_ctx* ctx, uint32_t flags) {
   return LAQ_OK;
 }
 
-int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, float* R_dev,
-                      uint8_t* upload_dev) {
-  if (!ctx) return LAQ_EINVAL;
+// sc says where the block partials of the passes live, sw is the grid that fits that many slots.
+static int quantize_skip_impl(laq_ctx* ctx, const char* who, const float* G_dev, uint32_t* codes_dev,
+                              float* R_dev, uint8_t* upload_dev, const DeviceScalars& sc, const Sweep& sw) {
   if (!G_dev || !codes_dev || !R_dev || !upload_dev)
-    return set_error(ctx, LAQ_EINVAL, "laq_quantize_skip: null pointer");
+    return set_error(ctx, LAQ_EINVAL, "%s: null pointer", who);
   if (((uintptr_t)G_dev | (uintptr_t)codes_dev) & 15)
-    return set_error(ctx, LAQ_EINVAL, "laq_quantize_skip: G_dev and codes_dev must be 16-byte aligned");
+    return set_error(ctx, LAQ_EINVAL, "%s: G_dev and codes_dev must be 16-byte aligned", who);
   QuantArgs a{};
   a.G = G_dev; a.H = ctx->H; a.codes = codes_dev; a.R_out = R_dev; a.upload = upload_dev;
-  a.sc = ctx->sc;
+  a.sc = sc;
   a.p = ctx->p; a.p_stride = ctx->p_stride; a.w_stride = ctx->w_stride;
   a.M = ctx->M; a.D = ctx->D; a.t_bar = ctx->t_bar; a.eps_K = ctx->eps_K;
-  a.slots = used_slots(ctx->p, ctx->M);
+  a.slots = sw.Gx;
   a.alpha = ctx->alpha; a.mode = ctx->mode;
-  const Sweep sw = make_sweep(ctx->p, ctx->M);
   const dim3 grid((unsigned)sw.Gx, (unsigned)ctx->M);
   a.U = sw.U;
   a.fused_decide = sw.Gx == 1;
@@ -1247,15 +1269,17 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
     // laq_worker_grads produced these gradients and left the block maxima of
     // |g - h| behind: the radius pass (a full read of g and h) is not needed
     a.rsrc = ctx->rprod; a.rstride = ctx->rprod_stride;
-    a.rcount = ctx->rprod_count <= 64 ? ctx->rprod_count : 0;   // > 64: Rfin was finished by the producer
+    a.rcount = ctx->rprod_count <= 64 ? ctx->rprod_count : 0;   // > 64: finished into Rhand when handed over
+    a.rfin = ctx->sc.Rhand;
   } else {
     hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
-                       ctx->p_stride, sw.U, a.slots, ctx->sc);
-    a.rsrc = ctx->sc.Rpart; a.rstride = a.slots;
+                       ctx->p_stride, sw.U, a.slots, sc);
+    a.rsrc = sc.Rpart; a.rstride = a.slots;
     a.rcount = sw.Gx <= 64 ? sw.Gx : 0;
+    a.rfin = sc.Rfin;
     if (a.rcount == 0)
       hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
-                         ctx->sc.Rpart, a.slots, sw.Gx, ctx->sc.Rfin);
+                         sc.Rpart, a.slots, sw.Gx, sc.Rfin);
   }
 #define LAQ_CALL(BB) launch_codes<BB>(grid, ctx->stream, a)
   LAQ_DISPATCH_B(ctx->b, LAQ_CALL)
@@ -1264,16 +1288,27 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   return LAQ_OK;
 }
 
+int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, float* R_dev,
+                      uint8_t* upload_dev) {
+  if (!ctx) return LAQ_EINVAL;
+  return quantize_skip_impl(ctx, "laq_quantize_skip", G_dev, codes_dev, R_dev, upload_dev, ctx->sc,
+                            make_sweep(ctx->p, partial_slots(ctx->M)));
+}
+
 int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_dev, int32_t count) {
   if (!ctx) return LAQ_EINVAL;
-  if (!G_dev || !rmax_dev || count < 1)
-    return set_error(ctx, LAQ_EINVAL, "laq_radius_handover: null pointer or count < 1");
+  if (count == 0) {            // withdraws a declaration (also the one laq_worker_grads leaves)
+    ctx->radius_for = nullptr;
+    return LAQ_OK;
+  }
+  if (!G_dev || !rmax_dev || count < 0)
+    return set_error(ctx, LAQ_EINVAL, "laq_radius_handover: null pointer or count < 0");
   ctx->rprod = const_cast<uint32_t*>(rmax_dev);
   ctx->rprod_stride = count;
   ctx->rprod_count = count;
   if (count > 64) {
     hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, ctx->rprod,
-                       count, count, ctx->sc.Rfin);
+                       count, count, ctx->sc.Rhand);
     LAQ_HIP(ctx, hipGetLastError());
   }
   ctx->radius_for = G_dev;
@@ -1295,7 +1330,7 @@ int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
   a.M = ctx->M; a.D = ctx->D; a.b = ctx->b; a.alpha = ctx->alpha;
   const int64_t blocks = server_blocks(ctx->p, &a.J);
   a.fused_finish = blocks <= 32;
-  const size_t smem = (size_t)ctx->M * 12;
+  const size_t smem = (size_t)(ctx->M < kServerList ? ctx->M : kServerList) * 12;
   const dim3 grid((unsigned)blocks);
 #define LAQ_CALL(BB) launch_server<BB>(grid, smem, ctx->stream, a)
   if (ctx->b == LAQ_B_EXACT) LAQ_CALL(kExact);
@@ -1429,7 +1464,7 @@ int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev) {
   if (st == LAQ_OK && ctx->rprod_count > 0) {
     if (ctx->rprod_count > 64) {
       hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
-                         ctx->rprod, ctx->rprod_stride, ctx->rprod_count, ctx->sc.Rfin);
+                         ctx->rprod, ctx->rprod_stride, ctx->rprod_count, ctx->sc.Rhand);
       LAQ_HIP(ctx, hipGetLastError());
     }
     ctx->radius_for = G_dev;

@@ -17,7 +17,9 @@ struct DeviceScalars {
   uint32_t* Rpart;              // [M][slots] block maxima of |g-h| (raw bits)
   unsigned long long* Spart;    // [M][slots] block sums of (2q-L)^2
   unsigned long long* Npart;    // [M][slots] block sums of the integer error squares
-  uint32_t* Rfin;               // [M] radius of the current call (raw bits)
+  uint32_t* Rfin;               // [M] radius found by the current call's own radius pass (raw bits)
+  uint32_t* Rhand;              // [M] radius finished from a producer's block maxima (hand-over); never
+                                //     written by a radius pass, so it stays valid as long as the hand-over does
   long long* Sq;                // [M] stash
   double* E2;                   // [M] stash
   double* lhs;                  // [M]

@@ -15,8 +15,11 @@
 #include <math.h>
 
 #include "laq_internal.h"
+#include "laq_tile_loader.h"
 
 namespace laq {
+
+static_assert(kLoaderThreads == kThreads, "the tile map assumes the matrix kernels' block size");
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -44,28 +47,7 @@ struct GemmArgs {
   int32_t nsplit, ksplit;
 };
 
-// Tile loaders.  An operand's block tile is BX wide and BK deep, BX BK / 4 float4 in all: lane t
-// moves the float4 numbered e = t + 256 i, i < NV = ceil(BX BK / 1024); when BX BK is not a
-// multiple of 1024 the last of them does not exist for some lanes.  LDS tiles are K-major: tile[kk][xx].
-template <int BX, int BK>
-struct TileMap {
-  static constexpr int kVec = BX * BK / 4;                       // float4 per tile
-  static constexpr int NV = (kVec + kThreads - 1) / kThreads;
-  static constexpr bool kExact = (kVec % kThreads) == 0;
-  static constexpr int TPR = BX / 4;                             // lanes per tile row (K-major source)
-  static constexpr int LPR = BK / 4;                             // lanes per source row (X-major source)
-  __device__ static __forceinline__ bool exists(int i) { return kExact || (int)threadIdx.x + kThreads * i < kVec; }
-  // K-major source S[k][x]: float4 e covers tile[kk][xx .. xx+3]
-  __device__ static __forceinline__ void kmajor(int i, int& kk, int& xx) {
-    const int e = (int)threadIdx.x + kThreads * i;
-    kk = e / TPR; xx = (e % TPR) * 4;
-  }
-  // X-major source S[x][k]: float4 e covers tile[kk .. kk+3][xx]
-  __device__ static __forceinline__ void xmajor(int i, int& kk, int& xx) {
-    const int e = (int)threadIdx.x + kThreads * i;
-    xx = e / LPR; kk = (e % LPR) * 4;
-  }
-};
+// Tile loaders (tile numbering and the aligned loader's addressing: laq_tile_loader.h).
 
 // K-major source S[k][x]
 template <int BX, int BK>
@@ -75,10 +57,10 @@ __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, i
 #pragma unroll
   for (int i = 0; i < TM::NV; ++i) {
     int kk, xx;
-    TM::kmajor(i, kk, xx);
+    TM::kmajor((int)threadIdx.x, i, kk, xx);
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (TM::exists(i) && k < K) {
+    if (TM::exists((int)threadIdx.x, i) && k < K) {
       const float* src = S + (int64_t)k * ld + x;
       if (vec && x + 3 < X) {
         v = *reinterpret_cast<const float4*>(src);
@@ -98,8 +80,8 @@ __device__ __forceinline__ void store_direct(float (*tile)[BX + 4], const float4
 #pragma unroll
   for (int i = 0; i < TM::NV; ++i) {
     int kk, xx;
-    TM::kmajor(i, kk, xx);
-    if (TM::exists(i)) *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
+    TM::kmajor((int)threadIdx.x, i, kk, xx);
+    if (TM::exists((int)threadIdx.x, i)) *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
   }
 }
 
@@ -111,10 +93,10 @@ __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int 
 #pragma unroll
   for (int i = 0; i < TM::NV; ++i) {
     int kk, xx;
-    TM::xmajor(i, kk, xx);
+    TM::xmajor((int)threadIdx.x, i, kk, xx);
     const int k = k0 + kk, x = x0 + xx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (TM::exists(i) && x < X) {
+    if (TM::exists((int)threadIdx.x, i) && x < X) {
       const float* src = S + (int64_t)x * ld + k;
       if (vec && k + 3 < K) {
         v = *reinterpret_cast<const float4*>(src);
@@ -134,8 +116,8 @@ __device__ __forceinline__ void store_transposed(float (*tile)[BX + 4], const fl
 #pragma unroll
   for (int i = 0; i < TM::NV; ++i) {
     int kk, xx;
-    TM::xmajor(i, kk, xx);
-    if (TM::exists(i)) {
+    TM::xmajor((int)threadIdx.x, i, kk, xx);
+    if (TM::exists((int)threadIdx.x, i)) {
       tile[kk + 0][xx] = r[i].x;
       tile[kk + 1][xx] = r[i].y;
       tile[kk + 2][xx] = r[i].z;
@@ -144,67 +126,33 @@ __device__ __forceinline__ void store_transposed(float (*tile)[BX + 4], const fl
   }
 }
 
-// Fast path (operand rows 16-byte aligned, X and K multiples of 4): every float4
-// is wholly inside or wholly outside the operand, so a lane keeps one clamped
-// source pointer per float4, loads unconditionally and zeroes what lies outside.
-// No branch sits between the loads and the matrix instructions they overlap.
+// Aligned operands: unconditional clamped loads (addresses: FastLoaderAddr in laq_tile_loader.h).
 template <int BX, int BK, bool XMAJOR>
 struct FastLoader {
-  using TM = TileMap<BX, BK>;
-  static constexpr int NV = TM::NV;
-  const float* q[NV];   // source address of this lane's float4 in the next K tile to load (clamped into the operand)
-  int kk[NV];           // its k offset inside the tile
-  bool xin[NV];         // its row/column lies inside the operand (false for a float4 that does not exist)
-  int64_t kstep;        // address advance per K tile
-  int64_t kunit;        // address advance per unit of k
-  int K;
-  bool all_in;          // the whole block tile lies inside the operand (uniform over the block)
-
-  __device__ __forceinline__ void init(const float* S, int64_t ld, int K_, int X, int x0) {
-    K = K_;
-    all_in = TM::kExact && x0 + BX <= X;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      int kq, xx;
-      if (XMAJOR) TM::xmajor(i, kq, xx); else TM::kmajor(i, kq, xx);
-      if (!TM::exists(i)) { kq = 0; xx = 0; }
-      kk[i] = kq;
-      const int x = x0 + xx;
-      xin[i] = TM::exists(i) && x < X;
-      const int xc = xin[i] ? x : 0;
-      q[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
-    }
-    kstep = XMAJOR ? BK : (int64_t)BK * ld;
-    kunit = XMAJOR ? 1 : ld;
+  FastLoaderAddr<BX, BK, XMAJOR> at;
+  static constexpr int NV = FastLoaderAddr<BX, BK, XMAJOR>::NV;
+  __device__ __forceinline__ void init(const float* S, int64_t ld, int K, int X, int x0) {
+    at.init((int)threadIdx.x, S, ld, K, X, x0);
   }
   // Loads K tile number `tile` (tiles are requested in order 0, 1, 2, ...) and advances the
-  // pointers.  In the last, partial tile, a float4 of k >= K is redirected to k = 0 .. 3 of its own
-  // row or column, which is inside the operand whatever K (K >= 4 on this path; its place in tile 0
-  // would not be when K < BK and the first tile is itself the partial one).
-  // Nothing here touches the loaded values, so the wave does not wait for them before it multiplies.
+  // pointers.  Nothing here touches the loaded values, so the wave does not wait for them before it
+  // multiplies.
   __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) {
-    const int k0 = tile * BK;
-    if (k0 + BK <= K) {                                   // uniform
+    if (at.is_whole(tile)) {                              // uniform
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        r[i] = *reinterpret_cast<const float4*>(q[i]);
-        q[i] += kstep;
-      }
+      for (int i = 0; i < NV; ++i) r[i] = *reinterpret_cast<const float4*>(at.whole(i));
+      at.advance();
     } else {
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const bool kin = k0 + kk[i] < K;
-        r[i] = *reinterpret_cast<const float4*>(kin ? q[i] : q[i] - (int64_t)tile * kstep - kk[i] * kunit);
-      }
+      for (int i = 0; i < NV; ++i) r[i] = *reinterpret_cast<const float4*>(at.partial(tile, i));
     }
   }
   // zeroes what lies outside the operand; called when the registers move to LDS
   __device__ __forceinline__ void mask(int tile, float4 (&r)[NV]) const {
-    const int k0 = tile * BK;
-    if (all_in && k0 + BK <= K) return;                   // uniform: interior tile, nothing to zero
+    if (at.all_in && at.is_whole(tile)) return;           // uniform: interior tile, nothing to zero
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const bool ok = (k0 + kk[i] < K) && xin[i];
+      const bool ok = at.keep(tile, i);
       float4 v = r[i];
       v.x = ok ? v.x : 0.0f; v.y = ok ? v.y : 0.0f; v.z = ok ? v.z : 0.0f; v.w = ok ? v.w : 0.0f;
       r[i] = v;

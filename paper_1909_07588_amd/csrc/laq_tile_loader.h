@@ -1,0 +1,96 @@
+// Tile addressing of the matrix kernels (laq_mlp.hip), in a form that also compiles for the host: the
+// kernels read operands with unconditional, clamped 16-byte loads, so that every address they form must
+// lie inside the operand for every tile shape, contraction length and width.  A host program walks the same
+// functions over all 256 lanes and all tiles and checks exactly that (tests/test_loader_addresses.py); the
+// lane number is therefore an argument, not threadIdx.x.
+#pragma once
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define LAQ_HD __host__ __device__ __forceinline__
+#else
+#define LAQ_HD inline
+#endif
+
+namespace laq {
+
+constexpr int kLoaderThreads = 256;   // lanes that share one tile (block size of the matrix kernels)
+
+// An operand's block tile is BX wide and BK deep, BX BK / 4 float4 in all: lane t moves the float4
+// numbered e = t + 256 i, i < NV = ceil(BX BK / 1024); when BX BK is not a multiple of 1024 the last of
+// them does not exist for some lanes.  LDS tiles are K-major: tile[kk][xx].
+template <int BX, int BK>
+struct TileMap {
+  static constexpr int kVec = BX * BK / 4;                       // float4 per tile
+  static constexpr int NV = (kVec + kLoaderThreads - 1) / kLoaderThreads;
+  static constexpr bool kExact = (kVec % kLoaderThreads) == 0;
+  static constexpr int TPR = BX / 4;                             // lanes per tile row (K-major source)
+  static constexpr int LPR = BK / 4;                             // lanes per source row (X-major source)
+  static LAQ_HD bool exists(int tid, int i) { return kExact || tid + kLoaderThreads * i < kVec; }
+  // K-major source S[k][x]: float4 e covers tile[kk][xx .. xx+3]
+  static LAQ_HD void kmajor(int tid, int i, int& kk, int& xx) {
+    const int e = tid + kLoaderThreads * i;
+    kk = e / TPR; xx = (e % TPR) * 4;
+  }
+  // X-major source S[x][k]: float4 e covers tile[kk .. kk+3][xx]
+  static LAQ_HD void xmajor(int tid, int i, int& kk, int& xx) {
+    const int e = tid + kLoaderThreads * i;
+    xx = e / LPR; kk = (e % LPR) * 4;
+  }
+};
+
+// Fast path (operand rows 16-byte aligned, X and K multiples of 4, K >= 4): every float4 is wholly inside
+// or wholly outside the operand, so a lane keeps one clamped source pointer per float4, loads
+// unconditionally and zeroes what lies outside.  No branch sits between the loads and the matrix
+// instructions they overlap.  This struct holds the addressing; the loads themselves are in the kernel.
+template <int BX, int BK, bool XMAJOR>
+struct FastLoaderAddr {
+  using TM = TileMap<BX, BK>;
+  static constexpr int NV = TM::NV;
+  const float* q[NV];   // source address of this lane's float4 in the next K tile to load (clamped into the operand)
+  int kk[NV];           // its k offset inside the tile
+  bool xin[NV];         // its row/column lies inside the operand (false for a float4 that does not exist)
+  int64_t kstep;        // address advance per K tile
+  int64_t kunit;        // address advance per unit of k
+  int K;
+  bool all_in;          // the whole block tile lies inside the operand (uniform over the block)
+
+  // S: operand, K-major S[k][x] (XMAJOR false) or X-major S[x][k]; ld: its row stride; the block tile
+  // starts at x0.
+  LAQ_HD void init(int tid, const float* S, int64_t ld, int K_, int X, int x0) {
+    K = K_;
+    all_in = TM::kExact && x0 + BX <= X;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      int kq, xx;
+      if (XMAJOR) TM::xmajor(tid, i, kq, xx); else TM::kmajor(tid, i, kq, xx);
+      if (!TM::exists(tid, i)) { kq = 0; xx = 0; }
+      kk[i] = kq;
+      const int x = x0 + xx;
+      xin[i] = TM::exists(tid, i) && x < X;
+      const int xc = xin[i] ? x : 0;
+      q[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
+    }
+    kstep = XMAJOR ? BK : (int64_t)BK * ld;
+    kunit = XMAJOR ? 1 : ld;
+  }
+  // Whole K tile `tile` (k0 + BK <= K): the address of float4 i; advance() follows every such tile.
+  LAQ_HD const float* whole(int i) const { return q[i]; }
+  LAQ_HD void advance() {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) q[i] += kstep;
+  }
+  // The last, partial tile (tiles are requested in order 0, 1, 2, ...; `tile` advances were made): a
+  // float4 of k >= K is redirected to k = 0 .. 3 of its own row or column, which is inside the operand
+  // whatever K (its place in tile 0 would not be when K < BK and the first tile is itself the partial one).
+  LAQ_HD const float* partial(int tile, int i) const {
+    const bool kin = tile * BK + kk[i] < K;
+    return kin ? q[i] : q[i] - (int64_t)tile * kstep - kk[i] * kunit;
+  }
+  LAQ_HD bool is_whole(int tile) const { return tile * BK + BK <= K; }
+  // whether float4 i of K tile `tile` holds operand data (else it is zeroed on the way to LDS)
+  LAQ_HD bool keep(int tile, int i) const { return (tile * BK + kk[i] < K) && xin[i]; }
+};
+
+}  // namespace laq

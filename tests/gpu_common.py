@@ -104,3 +104,23 @@ def check_server(ctx, st, theta, msgs, G, force=False, ring_rtol=None):
         ring_rtol = max(1e-13, 4.0 * p * 2.0 ** -53)
     assert np.allclose(d2, st.dtheta2, rtol=ring_rtol, atol=0.0), (d2, st.dtheta2)
     return out
+
+
+def check_model_grads(w, G, G_ref, theta, X, y, idx=None, workers=None, report=None, tag=""):
+    """Model gradients of the HIP path against the oracle's, per worker, within 1e-5 of the worker's
+    largest gradient entry.  The ReLU network has one discrete decision per hidden unit and sample
+    (z > 0) that binary32 and binary64 sums cannot share at |z| within rounding of zero: there the
+    comparison is the one relu_rule documents (flip a subset of the near-zero candidates, found by a
+    fit, then compare as usual).  idx[M][B]: the rows a minibatch call drew.  G, G_ref: [M][p], or
+    {m: g} for sampled workers."""
+    import relu_rule
+    ms = range(w.M) if workers is None else workers
+    for m in ms:
+        g, g_ref = G[m], G_ref[m]
+        if w.kind == 3:
+            Xm, ym = (X[m], y[m]) if idx is None else (X[m][idx[m]], y[m][idx[m]])
+            relu_rule.assert_network_gradients_close(g, g_ref, theta, Xm, ym, w.dims, w.M * len(ym),
+                                                     tag=f"{tag} worker {m}", report=report)
+        else:
+            err = np.abs(g - g_ref).max() / np.abs(g_ref).max()
+            assert err <= 1e-5, (tag, m, err)

@@ -3,16 +3,19 @@
 Headline workload (multinomial logistic regression 785x10, M = 10 x 6000): the whole loop against the
 oracle, with the samples tiled (as timed) and row-major; the stochastic variant (minibatch 500) on both
 small models likewise.  784-200-10 network at full size: gradients of sampled workers against the oracle.  The
-784-2048-2048-10 network (M = 32 x 8192) is too large for the oracle's plain loops, so its full-size
-launch is tied to launches the oracle does check by a property that holds at any size: a worker's
-full-batch gradient is the average of its minibatch gradients over a partition of its shard."""
+784-2048-2048-10 network (M = 32 x 8192), in the launch bench.py times: the gradients of sampled workers
+against the oracle's plain loops (a quarter of a TFLOP in binary64 per worker), then the quantizer, the skip
+rule and the server step on the GPU's own gradients against the oracle for all 32 workers; and a property that
+ties every worker to launches the oracle checks: a worker's full-batch gradient is the average of its minibatch
+gradients over a partition of its shard."""
 import numpy as np
 import pytest
 
 torch = pytest.importorskip("torch")
 import laq_synth
 import oracle
-from gpu_common import DEV, check_quantize, check_server, make_pair, push_state
+from gpu_common import (DEV, bits_equal, check_model_grads, check_quantize, check_server, make_pair,
+                        push_state)
 
 pytestmark = pytest.mark.gpu
 
@@ -42,8 +45,7 @@ def test_headline_workload_full_size_loop(tiled):
         torch.cuda.synchronize()
         G = Gd[:, :w.p].cpu().numpy()
         G_ref, _ = oracle.grads_all(w.kind, st.theta, X, y, w.dims, w.lam)
-        err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
-        assert err.max() <= 1e-5, (it, err)
+        check_model_grads(w, G, G_ref, st.theta, X, y, tag=f"iteration {it}")
         msgs, _ = check_quantize(ctx, st, Gd, G, msgs)
         check_server(ctx, st, theta, msgs, G)
         push_state(ctx, st)
@@ -66,8 +68,7 @@ def test_stochastic_variant_full_size_loop(cfg):
         torch.cuda.synchronize()
         G = Gd[:, :w.p].cpu().numpy()
         G_ref = oracle.grads_minibatch(w.kind, st.theta, X, y, w.dims, w.lam, idx)
-        err = np.abs(G - G_ref).max(axis=1) / np.abs(G_ref).max(axis=1)
-        assert err.max() <= 1e-5, (it, err)
+        check_model_grads(w, G, G_ref, st.theta, X, y, idx=idx, tag=f"iteration {it}")
         msgs, _ = check_quantize(ctx, st, Gd, G, msgs)
         check_server(ctx, st, theta, msgs, G)
         push_state(ctx, st)
@@ -85,10 +86,10 @@ def test_small_network_full_size_sampled_workers():
     torch.cuda.synchronize()
     G = Gd[:, :w.p].cpu().numpy()
     N = w.M * w.N_m
-    for m in (0, 7):
-        g_ref = oracle.grad_worker(w.kind, theta_h, X[m], y[m], w.dims, w.lam, N)
-        err = np.abs(G[m] - g_ref).max() / np.abs(g_ref).max()
-        assert err <= 1e-5, (m, err)
+    report = []
+    ref = {m: oracle.grad_worker(w.kind, theta_h, X[m], y[m], w.dims, w.lam, N) for m in (0, 7)}
+    check_model_grads(w, G, ref, theta_h, X, y, workers=(0, 7), report=report)
+    print("relu candidates / flips:", [(r[1], r[2]) for r in report])
 
 
 def test_largest_network_full_size_gradient_is_the_average_over_a_partition():
@@ -112,3 +113,68 @@ def test_largest_network_full_size_gradient_is_the_average_over_a_partition():
     err = ((mean - full).abs().amax(dim=1) / full.abs().amax(dim=1)).max().item()
     assert err <= 1e-5, err
     assert ctx.laq_get_counters()[2] == 0
+
+
+def test_largest_network_full_size_against_the_oracle():
+    """Workload 5 as bench.py runs it (M = 32 x 8192 samples, 784-2048-2048-10, b = 4), from a mid-run state:
+    the gradients of two sampled workers against the oracle; every worker's radius (handed over by the
+    weight-gradient epilogues), integer sums, both sides of (7a) and decision, and the packed codes of four
+    workers, against the oracle quantizing the GPU's gradients; then one server step, bit for bit."""
+    w = laq_synth.workload(5)
+    X, y, theta0 = laq_synth.model_inputs(w)
+    rng = np.random.default_rng(55)
+    theta_h = (theta0 + 0.01 * rng.standard_normal(w.p)).astype(np.float32)
+    ctx, st, theta = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta_h)
+    M, p, b = w.M, w.p, w.b
+    for m in range(M):                                       # mid-run stored gradients, worker by worker
+        st.H[m] = (2e-5 * rng.standard_normal(p)).astype(np.float32)
+    st.nabla[:] = st.H.sum(0)
+    st.Ehat2[:] = rng.random(M) * 1e-9
+    st.t[:] = rng.integers(0, w.t_bar + 1, M)
+    st.dtheta2[:] = rng.random(w.D) * 1e-10
+    push_state(ctx, st)
+    ctx.laq_set_model(w.kind, w.dims, w.lam)
+    ctx.laq_set_data(torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV))
+    Gd = ctx.alloc_G()
+    ctx.laq_worker_grads(theta, Gd)
+    codes, R, up = ctx.alloc_messages()
+    ctx.laq_quantize_skip(Gd, codes, R, up)                  # single pass: the radius comes from the epilogues
+    torch.cuda.synchronize()
+    G = Gd[:, :p].cpu().numpy()
+    # a1: sampled workers against the oracle's plain loops
+    sampled = (5, 30)
+    report = []
+    ref = {m: oracle.grad_worker(w.kind, theta_h, X[m], y[m], w.dims, w.lam, M * w.N_m) for m in sampled}
+    check_model_grads(w, G, ref, theta_h, X, y, workers=sampled, report=report)
+    print("relu candidates / flips:", [(r[1], r[2]) for r in report], flush=True)
+    del X, ref
+    # a2 + a3: all workers
+    sview = ctx.state()
+    R_h, up_h = R.cpu().numpy(), up.cpu().numpy()
+    Sq_h, E2_h = sview["Sq"].cpu().numpy(), sview["E2"].cpu().numpy()
+    lhs_h, rhs_h = sview["lhs"].cpu().numpy(), sview["rhs"].cpu().numpy()
+    nw = oracle.code_words(p, b)
+    with_codes = {0, 5, 17, 31}
+    for m in range(M):
+        o = oracle.quantize(G[m], st.H[m], b, want_vectors=(m in with_codes))
+        skip, rhs = oracle.skip(o["lhs"], o["E2"], st.Ehat2[m], st.xi, st.dtheta2, st.alpha, M, st.t[m], st.t_bar)
+        assert bits_equal(np.float32(R_h[m]), np.float32(o["R"])), m
+        assert int(Sq_h[m]) == o["Sq"] and bits_equal(np.float64(E2_h[m]), np.float64(o["E2"])), m
+        assert bits_equal(np.float64(lhs_h[m]), np.float64(o["lhs"])), m
+        assert bits_equal(np.float64(rhs_h[m]), np.float64(rhs)), m
+        assert int(up_h[m]) == int(not skip), m
+        if m in with_codes:
+            got = codes[m, :nw].cpu().numpy().view(np.uint32)
+            assert np.array_equal(got, oracle.pack(o["q"], b)), m
+    assert 0 < int(up_h.sum())                               # the server step below has rows to aggregate
+    # a4: one server step
+    out = st.iteration(G, want_codes=False)
+    ctx.laq_server_step(codes, R, up, theta)
+    torch.cuda.synchronize()
+    assert np.array_equal(up_h, out["upload"])
+    assert bits_equal(theta.cpu().numpy(), st.theta)
+    assert bits_equal(sview["nabla"][:p].cpu().numpy(), st.nabla)
+    for m in (0, 17, 31):
+        assert bits_equal(sview["H"][m, :p].cpu().numpy(), st.H[m]), m
+    assert np.array_equal(sview["t"].cpu().numpy(), st.t)
+    assert np.allclose(sview["dtheta2"].cpu().numpy(), st.dtheta2, rtol=4.0 * p * 2.0 ** -53, atol=0)

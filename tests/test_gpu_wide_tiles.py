@@ -10,7 +10,7 @@ import pytest
 torch = pytest.importorskip("torch")
 import laq_synth
 import oracle
-from gpu_common import DEV, make_pair
+from gpu_common import DEV, check_model_grads, make_pair
 
 pytestmark = pytest.mark.gpu
 
@@ -28,24 +28,13 @@ def _gradients(w, seed):
     return Gd[:, :w.p].cpu().numpy(), theta, X, y
 
 
-def _check_layers(dims, g, ref, tag):
-    assert np.abs(g - ref).max() <= 1e-5 * np.abs(ref).max(), tag
-    off = 0
-    for i in range(len(dims) - 1):
-        for n in (dims[i] * dims[i + 1], dims[i + 1]):
-            seg, r = g[off:off + n], ref[off:off + n]
-            assert np.abs(seg - r).max() <= 2e-5 * np.abs(r).max(), (tag, i, n)
-            off += n
-
-
 @pytest.mark.parametrize("dims,M,N_m", [((36, 200, 160, 10), 8, 4100),     # aligned: fast loaders
                                         ((37, 190, 150, 7), 8, 4099)])     # ragged: generic loaders
 def test_many_samples_forward_backward_and_split_weight_gradients(dims, M, N_m):
     w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, M, N_m, dims, laq_synth.mlp_param_count(dims), 8)
     G, theta, X, y = _gradients(w, 21)
-    for m in (0, M - 1):
-        ref = oracle.grad_worker(w.kind, theta, X[m], y[m], w.dims, w.lam, M * N_m)
-        _check_layers(dims, G[m], ref, m)
+    ref = {m: oracle.grad_worker(w.kind, theta, X[m], y[m], w.dims, w.lam, M * N_m) for m in (0, M - 1)}
+    check_model_grads(w, G, ref, theta, X, y, workers=(0, M - 1))       # overall and per parameter block
 
 
 @pytest.mark.parametrize("dims,M,N_m", [((1024, 200, 10), 96, 16), ((1022, 190, 10), 96, 15)])
@@ -53,5 +42,4 @@ def test_many_workers_unsplit_weight_gradients(dims, M, N_m):
     w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, M, N_m, dims, laq_synth.mlp_param_count(dims), 8)
     G, theta, X, y = _gradients(w, 22)
     G_ref, _ = oracle.grads_all(w.kind, theta, X, y, w.dims, w.lam)
-    for m in range(M):
-        _check_layers(dims, G[m], G_ref[m], m)
+    check_model_grads(w, G, G_ref, theta, X, y)

@@ -241,6 +241,25 @@ int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_d
 int laq_server_step(laq_ctx* ctx, const uint32_t* codes_dev, const float* R_dev,
                     const uint8_t* upload_dev, float* theta_dev);
 
+/*
+ * laq_quantize_skip for callers that can neither allocate device memory nor
+ * bring scratch for the passes' partial results: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * arithmetic, outputs and radius hand-over as laq_quantize_skip; the block
+ * partials of the radius and code passes (maxima of |g - h|, the two integer
+ * sums) live in a static device array of the library, 1.3 MB per GPU, held
+ * until the process ends, instead of the workspace.  The call allocates
+ * nothing.  Limits: M <= 4096 and ceil(p / 2048) <= 512 * floor(65536 / M)
+ * (65536 block partials in all, each covering at most 512 tiles of 2048
+ * coordinates); larger sizes return LAQ_EINVAL and enqueue nothing.  All
+ * contexts on one GPU share that GPU's array: calls of this function that
+ * overlap in time on one GPU (different streams or host threads) race on it,
+ * even on different contexts.  Every slot a call reads it has written itself,
+ * so nothing needs clearing between calls.
+ */
+int laq_quantize_skip_noalloc(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev,
+                              float* R_dev, uint8_t* upload_dev);
+
 /* Device pointers into the workspace (valid until laq_destroy).  The caller
  * may read or overwrite them between calls with stream-ordered copies; this
  * is how a checkpoint is saved, restored, or a reference state is imposed.

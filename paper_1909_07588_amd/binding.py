@@ -15,7 +15,8 @@ B_EXACT = 32          # laq_create's b for the identity quantizer (LAG / GD)
 EXPORTS = ["laq_p_stride", "laq_w_stride", "laq_workspace_bytes", "laq_create", "laq_destroy",
            "laq_reset", "laq_set_mode", "laq_set_model", "laq_model_workspace_bytes",
            "laq_set_data", "laq_tiled_data_bytes", "laq_tile_data", "laq_worker_grads", "laq_minibatch_workspace_bytes",
-           "laq_worker_grads_minibatch", "laq_quantize_skip", "laq_radius_handover", "laq_server_step",
+           "laq_worker_grads_minibatch", "laq_quantize_skip", "laq_quantize_skip_noalloc", "laq_radius_handover",
+           "laq_server_step",
            "laq_get_state", "laq_get_counters", "laq_last_error"]
 
 
@@ -79,6 +80,8 @@ def lib():
         L.laq_worker_grads_minibatch.argtypes = [vp, vp, vp, i64, vp, sz, vp]
         L.laq_quantize_skip.restype = C.c_int
         L.laq_quantize_skip.argtypes = [vp, vp, vp, vp, vp]
+        L.laq_quantize_skip_noalloc.restype = C.c_int
+        L.laq_quantize_skip_noalloc.argtypes = [vp, vp, vp, vp, vp]
         L.laq_radius_handover.restype = C.c_int
         L.laq_radius_handover.argtypes = [vp, vp, vp, C.c_int32]
         L.laq_server_step.restype = C.c_int
@@ -249,6 +252,10 @@ class Laq:
     def laq_quantize_skip(self, G, codes, R, upload):
         self._chk(self.L.laq_quantize_skip(self.h, C.c_void_p(G.data_ptr()), C.c_void_p(codes.data_ptr()),
                                            C.c_void_p(R.data_ptr()), C.c_void_p(upload.data_ptr())))
+
+    def laq_quantize_skip_noalloc(self, G, codes, R, upload):
+        self._chk(self.L.laq_quantize_skip_noalloc(self.h, C.c_void_p(G.data_ptr()), C.c_void_p(codes.data_ptr()),
+                                                   C.c_void_p(R.data_ptr()), C.c_void_p(upload.data_ptr())))
 
     def laq_radius_handover(self, G, rmax):
         """rmax: uint32 (or int32) device tensor [M][count], raw bits of block maxima of |g - h|;

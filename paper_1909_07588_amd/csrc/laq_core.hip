@@ -14,6 +14,7 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "laq_internal.h"
@@ -1132,6 +1133,42 @@ static MinibatchLayout minibatch_layout(const laq_ctx* ctx, int64_t B) {
   return l;
 }
 
+// ------------------------------------------------------------------ static scratch (laq_quantize_skip_noalloc)
+//
+// Block partials of the two streaming passes for callers that bring no scratch memory: a
+// file-scope device array, one copy per GPU, held until the process ends.  In host code the
+// array's name is only a handle; its device address comes from hipGetSymbolAddress, once per
+// device (resolve_static_scratch), and host code uses that address everywhere.
+constexpr int kStaticSlots = 65536;   // block partials in all (M * blocks per worker)
+constexpr int kStaticMaxM = 4096;     // workers
+struct StaticScratch {
+  unsigned long long Spart[kStaticSlots];
+  unsigned long long Npart[kStaticSlots];
+  uint32_t Rpart[kStaticSlots];
+  uint32_t Rfin[kStaticMaxM];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices] = {nullptr};
+static std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of the array; `device` must be the current device.
+static hipError_t resolve_static_scratch(int device, unsigned char** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+
 }  // namespace laq
 
 using namespace laq;
@@ -1217,6 +1254,8 @@ int laq_create(laq_ctx** out, int32_t M, int64_t p, int32_t b, int32_t D, const 
   e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
   if (e != hipSuccess || n_cu <= 0) return fail(LAQ_EDEVICE);
   ctx->n_cu = n_cu;
+  e = resolve_static_scratch(ctx->device, &ctx->static_scratch);   // this device is current
+  if (e != hipSuccess) return fail(LAQ_EDEVICE);
 
   double xi64[4096];
   for (int d = 0; d < D; ++d) xi64[d] = (double)xi[d];
@@ -1241,7 +1280,8 @@ int laq_set_mode(laq_ctx* ctx, uint32_t flags) {
   return LAQ_OK;
 }
 
-// sc says where the block partials of the passes live, sw is the grid that fits that many slots.
+// Both entry points of the quantizer: sc says where the block partials of the passes live (the
+// workspace, or this GPU's static array), sw is the grid that fits that many slots.
 static int quantize_skip_impl(laq_ctx* ctx, const char* who, const float* G_dev, uint32_t* codes_dev,
                               float* R_dev, uint8_t* upload_dev, const DeviceScalars& sc, const Sweep& sw) {
   if (!G_dev || !codes_dev || !R_dev || !upload_dev)
@@ -1293,6 +1333,25 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, flo
   if (!ctx) return LAQ_EINVAL;
   return quantize_skip_impl(ctx, "laq_quantize_skip", G_dev, codes_dev, R_dev, upload_dev, ctx->sc,
                             make_sweep(ctx->p, partial_slots(ctx->M)));
+}
+
+int laq_quantize_skip_noalloc(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev, float* R_dev,
+                              uint8_t* upload_dev) {
+  if (!ctx) return LAQ_EINVAL;
+  if (ctx->M > kStaticMaxM)
+    return set_error(ctx, LAQ_EINVAL, "laq_quantize_skip_noalloc: M = %d exceeds the static scratch (at most %d workers)",
+                     ctx->M, kStaticMaxM);
+  if (!ctx->static_scratch)
+    return set_error(ctx, LAQ_ESTATE, "laq_quantize_skip_noalloc: the static scratch of this device was not resolved");
+  const Sweep sw = make_sweep(ctx->p, kStaticSlots / ctx->M);
+  if (sw.U > 512)
+    return set_error(ctx, LAQ_EINVAL,
+                     "laq_quantize_skip_noalloc: M * p = %d * %lld exceeds the static scratch (%d block partials "
+                     "of at most 512 tiles of 2048 coordinates)", ctx->M, (long long)ctx->p, kStaticSlots);
+  StaticScratch* ss = reinterpret_cast<StaticScratch*>(ctx->static_scratch);
+  DeviceScalars sc = ctx->sc;
+  sc.Rpart = ss->Rpart; sc.Spart = ss->Spart; sc.Npart = ss->Npart; sc.Rfin = ss->Rfin;
+  return quantize_skip_impl(ctx, "laq_quantize_skip_noalloc", G_dev, codes_dev, R_dev, upload_dev, sc, sw);
 }
 
 int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_dev, int32_t count) {

@@ -60,6 +60,8 @@ struct laq_ctx {
   float* nabla = nullptr;
   laq::DeviceScalars sc{};
   size_t scalars_offset = 0, scalars_bytes = 0;
+  // device address of this GPU's static scratch array (laq_quantize_skip_noalloc), resolved by laq_create
+  unsigned char* static_scratch = nullptr;
 
   // Radius hand-over from laq_worker_grads to laq_quantize_skip: the gradient
   // kernels' epilogues leave block maxima of |g - h| in rprod[m][0..rprod_count);

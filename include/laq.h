@@ -220,9 +220,9 @@ int laq_quantize_skip(laq_ctx* ctx, const float* G_dev, uint32_t* codes_dev,
  * (G_dev and rmax_dev are then ignored).  A laq_quantize_skip on another G_dev
  * in between runs its own radius pass and leaves the declaration intact.  The
  * caller must withdraw it before it changes the contents of G_dev.
- * rmax_dev (device, caller-owned): with count <= 64 it is read by each such
+ * rmax_dev (device, caller-owned): with count <= 256 it is read by each such
  * laq_quantize_skip and must stay alive and unchanged until then; with count >
- * 64 it is read by a kernel this call enqueues on the stream (the maxima are
+ * 256 it is read by a kernel this call enqueues on the stream (the maxima are
  * combined once into the workspace) and may be reused after that.  The values
  * are trusted: if their maximum is not ||g_m - h_m||_inf the codes are those of
  * eq. 5 for that other radius, clamped to [0, L].  count >= 0.

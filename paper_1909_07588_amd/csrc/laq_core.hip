@@ -198,7 +198,16 @@ __global__ __launch_bounds__(kThreads) void radius_final_kernel(const uint32_t* 
   __shared__ uint32_t sm[kThreads / 64];
   const int m = blockIdx.x;
   uint32_t mx = 0;
-  for (int i = threadIdx.x; i < count; i += kThreads) mx = max(mx, src[(int64_t)m * stride + i]);
+  // eight unconditional loads in flight per thread, from clamped indices (a repeat does not change a
+  // maximum): a plain loop pays one memory latency per partial
+  const uint32_t* row = src + (int64_t)m * stride;
+  for (int i0 = threadIdx.x; i0 < count; i0 += 8 * kThreads) {
+    uint32_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = row[i0 + u * kThreads < count ? i0 + u * kThreads : i0];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) mx = max(mx, v[u]);
+  }
   mx = wave_max_u32(mx);
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = mx;
   __syncthreads();
@@ -217,7 +226,7 @@ struct QuantArgs {
   int64_t p, p_stride, w_stride;
   int32_t M, D, t_bar, eps_K, slots, U;
   int32_t fused_decide;   // 1: one block per worker, which applies the skip rule itself
-  // radius source: either the finished value rfin[m] (rcount == 0) or at most 64
+  // radius source: either the finished value rfin[m] (rcount == 0) or at most kDirectPartials
   // block maxima rsrc[m * rstride + i], i < rcount, combined on the fly
   const uint32_t* rsrc;
   const uint32_t* rfin;
@@ -226,6 +235,7 @@ struct QuantArgs {
   uint32_t mode;
 };
 
+constexpr int kDirectPartials = 256;   // block maxima that the code pass combines itself (4 per lane)
 constexpr int kMaxHistLds = 256;   // history terms staged in LDS (longer histories fall back to global reads)
 
 // Stages xi_d * dtheta2[d] for d < min(D, kMaxHistLds) in LDS; every thread of the block calls it.
@@ -354,8 +364,12 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void codes_kernel(Q
     uint8_t* out = reinterpret_cast<uint8_t*>(a.codes + (int64_t)m * a.w_stride);
     uint32_t rbits;
     if (a.rcount > 0) {
+      // four unconditional loads from clamped indices (duplicates do not change a maximum)
       const int lane = threadIdx.x & 63;
-      rbits = a.rsrc[(int64_t)m * a.rstride + (lane < a.rcount ? lane : 0)];   // (duplicates do not change a maximum)
+      const uint32_t* rs = a.rsrc + (int64_t)m * a.rstride;
+      const uint32_t r0 = rs[lane < a.rcount ? lane : 0], r1 = rs[lane + 64 < a.rcount ? lane + 64 : 0];
+      const uint32_t r2 = rs[lane + 128 < a.rcount ? lane + 128 : 0], r3 = rs[lane + 192 < a.rcount ? lane + 192 : 0];
+      rbits = max(max(r0, r1), max(r2, r3));
     } else {
       rbits = a.rfin[m];
     }
@@ -491,9 +505,20 @@ __device__ __forceinline__ void decide_worker(const QuantArgs& a, int m, int32_t
   stage_history(a, hterm);
   unsigned long long s64 = 0, n64 = 0;
   uint32_t rb = 0;
-  for (int i = threadIdx.x; i < n_slots; i += kThreads) {
-    s64 += __hip_atomic_load(&a.sc.Spart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    n64 += __hip_atomic_load(&a.sc.Npart[(int64_t)m * a.slots + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // Four slots of each sum in flight per thread (unconditional loads from clamped indices; the sums
+  // are integers, so the order is free): a plain loop pays a memory latency per slot.
+  const unsigned long long* Sp = a.sc.Spart + (int64_t)m * a.slots;
+  const unsigned long long* Np = a.sc.Npart + (int64_t)m * a.slots;
+  for (int i0 = threadIdx.x; i0 < n_slots; i0 += 4 * kThreads) {
+    unsigned long long sv[4], nv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kThreads < n_slots ? i0 + u * kThreads : i0;
+      sv[u] = Sp[i]; nv[u] = Np[i];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i0 + u * kThreads < n_slots) { s64 += sv[u]; n64 += nv[u]; }
   }
   if (a.rcount > 0) {
     if ((int)threadIdx.x < a.rcount) rb = a.rsrc[(int64_t)m * a.rstride + threadIdx.x];
@@ -651,7 +676,7 @@ template <int B, int NT>
 __device__ __forceinline__ void server_finish(const ServerArgs& a, int n_blocks, const FinishFetch& f,
                                               const double* own_total);
 
-constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane
+constexpr int kServerJ = 4;   // groups of 8 coordinates owned by one lane, at most
 constexpr int kServerList = 4096;   // workers per round of the server step (12 bytes of LDS each)
 
 // eq. 4: nabla^k = nabla^{k-1} + sum_{m in M^k} deltaQ_m, theta^{k+1} = theta^k - alpha nabla^k,
@@ -659,7 +684,10 @@ constexpr int kServerList = 4096;   // workers per round of the server step (12 
 // Worker-major: a lane owns up to 4 groups of 8 coordinates for the whole
 // kernel and keeps their running sums in registers, so the grid sweeps one
 // uploading worker's row at a time (one read stream, one write stream) in
-// ascending m -- the order in which the sums are defined.
+// ascending m -- the order in which the sums are defined.  A block's J NT
+// groups are one contiguous stretch of the row (its J slices side by side:
+// 5.10 TB/s in a full round of 64 workers x 2^24 coordinates, against 4.96 with
+// the slices a whole grid apart and 4.99 with blocks of 1024 threads).
 // SOLO: the grid is this one block. It then fetches nabla, theta and what the bookkeeping reads
 // at the start, so that a call on a small model pays for three dependent memory round trips
 // (upload flags, message rows, stores) instead of seven.
@@ -676,8 +704,8 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void server_kernel(
   __shared__ int n_up_s;
 
   const int64_t nfull = a.p / kGroup;
-  const int64_t span = (int64_t)gridDim.x * NT;
-  const int64_t grp0 = (int64_t)blockIdx.x * NT + threadIdx.x;
+  const int64_t span = NT;                                             // slice j of the block's stretch
+  const int64_t grp0 = (int64_t)blockIdx.x * a.J * NT + threadIdx.x;
   float4 pn[JN][2], pt[JN][2];
   float tn[kGroup - 1], tt[kGroup - 1];            // the p % 8 coordinates after the last whole group
   FinishFetch ff;
@@ -890,7 +918,10 @@ __global__ __launch_bounds__(SOLO ? kSoloThreads : kThreads) void server_kernel(
     server_finish<B, NT>(a, 1, ff, &total_s);
   } else {
     if (threadIdx.x == 0) {
-      a.sc.srv_part[blockIdx.x] = (smd[0] + smd[1]) + (smd[2] + smd[3]);
+      double tot = 0.0;
+#pragma unroll
+      for (int wv = 0; wv < NT / 64; wv += 4) tot += (smd[wv] + smd[wv + 1]) + (smd[wv + 2] + smd[wv + 3]);   // fixed order
+      a.sc.srv_part[blockIdx.x] = tot;
       if (a.fused_finish) {
         __threadfence();
         last_s = (atomicAdd(a.sc.srv_ticket, 1u) == gridDim.x - 1);
@@ -1309,13 +1340,13 @@ static int quantize_skip_impl(laq_ctx* ctx, const char* who, const float* G_dev,
     // laq_worker_grads produced these gradients and left the block maxima of
     // |g - h| behind: the radius pass (a full read of g and h) is not needed
     a.rsrc = ctx->rprod; a.rstride = ctx->rprod_stride;
-    a.rcount = ctx->rprod_count <= 64 ? ctx->rprod_count : 0;   // > 64: finished into Rhand when handed over
+    a.rcount = ctx->rprod_count <= kDirectPartials ? ctx->rprod_count : 0;   // more: finished into Rhand when handed over
     a.rfin = ctx->sc.Rhand;
   } else {
     hipLaunchKernelGGL(radius_kernel, grid, dim3(kThreads), 0, ctx->stream, G_dev, ctx->H, ctx->p,
                        ctx->p_stride, sw.U, a.slots, sc);
     a.rsrc = sc.Rpart; a.rstride = a.slots;
-    a.rcount = sw.Gx <= 64 ? sw.Gx : 0;
+    a.rcount = sw.Gx <= kDirectPartials ? sw.Gx : 0;
     a.rfin = sc.Rfin;
     if (a.rcount == 0)
       hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
@@ -1365,7 +1396,7 @@ int laq_radius_handover(laq_ctx* ctx, const float* G_dev, const uint32_t* rmax_d
   ctx->rprod = const_cast<uint32_t*>(rmax_dev);
   ctx->rprod_stride = count;
   ctx->rprod_count = count;
-  if (count > 64) {
+  if (count > kDirectPartials) {
     hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, ctx->rprod,
                        count, count, ctx->sc.Rhand);
     LAQ_HIP(ctx, hipGetLastError());
@@ -1521,7 +1552,7 @@ int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev) {
   ctx->radius_for = nullptr;
   const int st = worker_grads(ctx, theta_dev, G_dev);
   if (st == LAQ_OK && ctx->rprod_count > 0) {
-    if (ctx->rprod_count > 64) {
+    if (ctx->rprod_count > kDirectPartials) {
       hipLaunchKernelGGL(radius_final_kernel, dim3((unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
                          ctx->rprod, ctx->rprod_stride, ctx->rprod_count, ctx->sc.Rhand);
       LAQ_HIP(ctx, hipGetLastError());

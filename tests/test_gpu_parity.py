@@ -50,7 +50,9 @@ def test_one_iteration_from_a_random_state(b, M, p):
     check_server(ctx, st, theta, msgs, G)
 
 
-@pytest.mark.parametrize("b,p", [(2, 300_007), (4, (1 << 20) + 5), (8, 1_000_003), (3, 524_288)])
+@pytest.mark.parametrize("b,p", [(2, 300_007), (4, (1 << 20) + 5), (8, 1_000_003), (3, 524_288),
+                                 # 4096 tiles per worker: thousands of block partials per sum
+                                 (4, (1 << 23) + 13), (5, (1 << 23))])
 def test_many_tiles_and_ragged_tail(b, p):
     rng = np.random.default_rng(b * 7 + p)
     M = 5
@@ -581,7 +583,8 @@ def test_planted_near_zero_preactivations_pass_under_the_relu_rule():
         assert naive <= 1e-5
 
 
-@pytest.mark.parametrize("M,p,b,count", [(5, 300_007, 4, 37), (3, 4100, 3, 1), (4, 70_001, 8, 200), (10, 7850, 3, 64)])
+@pytest.mark.parametrize("M,p,b,count", [(5, 300_007, 4, 37), (3, 4100, 3, 1), (4, 70_001, 8, 200), (10, 7850, 3, 64),
+                                         (3, 700_001, 4, 256), (3, 700_001, 4, 257), (2, 50_000, 2, 1000)])
 def test_radius_handed_over_by_the_caller(M, p, b, count):
     """A caller's own producer of gradients leaves block maxima of |g - h| (here: torch ops on the
     library's stored gradients, over an uneven partition of the coordinates); laq_quantize_skip then
@@ -649,9 +652,10 @@ def test_radius_handed_over_by_the_gradient_kernels_is_dropped_when_the_state_ch
 
 def test_radius_of_the_gradient_kernels_survives_a_quantizer_call_on_other_gradients():
     """laq_worker_grads(G1), laq_quantize_skip(G2), laq_quantize_skip(G1), at a size where both the
-    producer's block maxima (> 64 per worker) and the radius pass's (> 64 blocks per worker) are
-    finished into a per-worker radius: the call on G2 must not disturb the radius handed over for G1."""
-    w = laq_synth.workload(3, scale=0.02)               # 784-200-10: p = 159 010, 78 blocks per worker
+    producer's block maxima and the radius pass's (each more than 256 per worker) are finished into
+    a per-worker radius: the call on G2 must not disturb the radius handed over for G1."""
+    dims = (784, 700, 10)                               # p = 556 510: 272 blocks per worker in the radius pass
+    w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, 4, 96, dims, laq_synth.mlp_param_count(dims), 8)
     X, y, theta0 = laq_synth.model_inputs(w)
     ctx, st, theta = make_pair(w.M, w.p, w.b, D=w.D, xi=w.xi, t_bar=w.t_bar, alpha=w.alpha, theta0=theta0)
     rng = np.random.default_rng(31)

@@ -81,7 +81,7 @@ def test_two_calls_in_a_row_the_second_smaller():
 
 
 @pytest.mark.parametrize("M,p,b", [(5, 300_007, 4), (1, 1, 1), (10, 7850, 3), (70, 40_003, 8), (2, 2_500_000, 2),
-                                   (6, 70_001, 32)])
+                                   (6, 70_001, 32), (3, (1 << 23) + 8, 4)])
 def test_shapes_against_the_existing_entry_point_and_the_oracle(M, p, b):
     rng = np.random.default_rng(M * 13 + p)
     ctx, st, theta = make_pair(M, p, b, D=4, t_bar=6, alpha=0.05)

@@ -12,6 +12,7 @@
 #include <math.h>
 
 #include "laq_internal.h"
+#include "laq_tile_loader.h"
 
 namespace laq {
 
@@ -153,8 +154,8 @@ __global__ __launch_bounds__(kThreads) void softmax_grad_kernel(
 // kernel.  LDS (two slice buffers, two partial-logit buffers: about 135 KB) and
 // registers allow one block per CU.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-constexpr int kRT = 16;          // rows per tile
-constexpr int kSmxWaves = 16;
+constexpr int kRT = kSmxRowsPerTile;          // rows per tile
+constexpr int kSmxWaves = kSmxWavesPerBlock;
 
 // Block barrier that orders LDS accesses only (the waves of the softmax kernel exchange nothing through
 // global memory inside the loop): the general __syncthreads() would also wait for every buffer load in
@@ -255,11 +256,10 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   int ix_next = 0, iy_next = 0;
   auto iload = [&](int64_t r0) {
     if constexpr (GATHER) {
-      const int64_t rb = r0 < r_end ? r0 : r_end - 1;
-      const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
-      const int yrow = 4 * (wave & 3) + lq;
-      ix_next = idxm[rb + (l16 < rows_valid ? l16 : rows_valid - 1)];
-      iy_next = idxm[rb + (yrow < rows_valid ? yrow : rows_valid - 1)];
+      const int64_t rb = smx_tile_row(r0, r_end);
+      const int rows_valid = smx_rows_valid(rb, r_end);
+      ix_next = idxm[rb + smx_data_row(l16, rows_valid)];
+      iy_next = idxm[rb + smx_label_row(wave, lq, rows_valid)];
     }
   };
   // Where the tile starting at row r0 lies: a per-lane pointer to the lane's 16 bytes of chunk
@@ -273,8 +273,8 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
   };
   auto gaddr = [&](int64_t r0) {
     // uniform tile base + 32-bit lane offsets (few address registers)
-    int64_t rb = r0 < r_end ? r0 : r_end - 1;                 // first row of the tile, clamped
-    const int rows_valid = (int)(r_end - rb < kRT ? r_end - rb : kRT);
+    const int64_t rb = smx_tile_row(r0, r_end);               // first row of the tile, clamped
+    const int rows_valid = smx_rows_valid(rb, r_end);
     TileAddr A;
     if constexpr (GATHER) {
       int ix = ix_next, iy = iy_next;
@@ -289,36 +289,32 @@ __global__ __launch_bounds__(64 * kSmxWaves) void softmax_grad_mfma_kernel(
     } else if constexpr (TILED) {
       A.base = Xm + (rb / kRT) * ((int64_t)nchunk * 256);           // (blocks start on tile boundaries)
       A.row_off = 0;
-      const int yrow = 4 * (wave & 3) + lq;
-      A.ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
+      A.ysrc = rb + smx_label_row(wave, lq, rows_valid);
       // Byte offset, within the worker's tiled shard, of chunk `wave` of the tile (of chunk 0 for a wave
       // past the tile's last chunk).  It is the same in all lanes: the loads are buffer loads that take
       // it from a scalar register and add the lane's constant 16 l themselves, so no vector instruction
       // computes an address (each one costs this kernel a matrix-instruction slot).
       A.base = Xm;
       A.lanep = Xm;
-      A.row_off = (uint32_t)(rb / kRT) * (uint32_t)(nchunk * 1024) + 1024u * (uint32_t)(wave < nchunk ? wave : 0);
+      A.row_off = smx_tiled_tile_off(rb, nchunk, wave);
       return A;
     } else {
       A.base = Xm + rb * ldx;
-      A.row_off = (uint32_t)(l16 < rows_valid ? l16 : rows_valid - 1) * (uint32_t)ldx;
-      const int yrow = 4 * (wave & 3) + lq;                         // softmax waves 0..3: rows 4 wave + lq
-      A.ysrc = rb + (yrow < rows_valid ? yrow : rows_valid - 1);
+      A.row_off = (uint32_t)smx_data_row(l16, rows_valid) * (uint32_t)ldx;
+      A.ysrc = rb + smx_label_row(wave, lq, rows_valid);
     }
-    A.lanep = A.base + (A.row_off + 4u * (4u * (uint32_t)wave + (uint32_t)lq));
+    A.lanep = A.base + (A.row_off + smx_lane_col(wave, lq));
     return A;
   };
   auto gchunk = [&](int n, const TileAddr& A) {
     if constexpr (TILED) {
       // chunk wave + 16 n lies 16 KB further per n; one past the tile's last chunk reads the wave's first instead
-      const uint32_t off = A.row_off + ((n < NFULL || wave + NW * n < nchunk) ? 1024u * NW * n : 0u);
+      const uint32_t off = smx_tiled_chunk_off(A.row_off, n, NFULL, wave, nchunk);
       const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(tiled_rsrc, (int)lane_bytes, (int)off, 0);
       return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3]));
     }
-    if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + 16 * NW * n);
-    uint32_t q = 4u * (uint32_t)(wave + NW * n) + (uint32_t)lq;     // float4 column
-    q = q < (uint32_t)nf4r ? q : 0u;
-    return *reinterpret_cast<const float4*>(A.base + (A.row_off + 4u * q));
+    if (n < NFULL) return *reinterpret_cast<const float4*>(A.lanep + smx_chunk_step(n));
+    return *reinterpret_cast<const float4*>(A.base + (A.row_off + smx_ragged_col(wave, n, lq, nf4r)));
   };
 
   floatx4 acc2[TMAX];
@@ -617,14 +613,7 @@ static size_t softmax_mfma_lds(const laq_ctx* ctx) {
 static int logistic_blocks(const laq_ctx* ctx, int64_t N_m, int* rows_per_block) {
   if (softmax_mfma_lds(ctx)) {
     // one block per CU at most (LDS-bound occupancy), whole row tiles per block
-    const int RT = kRT;
-    int64_t want = ctx->n_cu / ctx->M;
-    if (want < 1) want = 1;
-    const int64_t tiles = (N_m + RT - 1) / RT;
-    if (want > tiles) want = tiles;
-    const int64_t tpb = (tiles + want - 1) / want;
-    *rows_per_block = (int)(tpb * RT);
-    return (int)((tiles + tpb - 1) / tpb);
+    return smx_blocks(ctx->n_cu, ctx->M, N_m, rows_per_block);
   }
   // about two blocks per CU over all workers, at least 4 rows per wave
   int64_t want = ((int64_t)ctx->n_cu * 2 + ctx->M - 1) / ctx->M;
@@ -721,9 +710,10 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     // the tiled copy stands for the rows it was made from (a minibatch call binds other rows)
     const bool tiled = ctx->Xtiled && !ctx->gather_idx && ctx->tiled_for == ctx->X && ctx->tiled_rows == ctx->N_m;
     // chunks n < nfull exist for every wave and hold no column >= F (the tiled copy is zero there)
-    const int nfull = (tiled ? nchunk : ctx->F / 16) / kSmxWaves;
-    if (nchunk <= kSmxWaves) { if (nfull >= 1) LAQ_SMM(1, 1); else LAQ_SMM(1, 0); }
-    else if (nchunk <= 2 * kSmxWaves) { if (nfull >= 2) LAQ_SMM(2, 2); else LAQ_SMM(2, 1); }
+    int tmax, nfull;
+    smx_variant(ctx->F, tiled, tmax, nfull);
+    if (tmax == 1) { if (nfull >= 1) LAQ_SMM(1, 1); else LAQ_SMM(1, 0); }
+    else if (tmax == 2) { if (nfull >= 2) LAQ_SMM(2, 2); else LAQ_SMM(2, 1); }
     else if (nfull >= 4) LAQ_SMM(4, 4);
     else if (nfull == 3) LAQ_SMM(4, 3);
     else LAQ_SMM(4, 2);

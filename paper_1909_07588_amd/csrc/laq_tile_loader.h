@@ -94,3 +94,69 @@ struct FastLoaderAddr {
 };
 
 }  // namespace laq
+
+// ------------------------------------------------------------------ softmax-regression kernel (laq_grads.hip)
+//
+// Addressing of the matrix-core softmax-regression kernel's tile loads, shared with the host for the
+// same reason.  A block of 16 wavefronts walks tiles of 16 rows; lane (l16 = row, lq = quarter) of wave w
+// takes 16 bytes of each chunk w + 16 n (16 columns) of its row.  Tiles the prologue requests past the
+// block's row range are clamped to its last row, rows past a ragged last tile to the tile's last row,
+// and a chunk that may cross column F is clamped into the row; what was clamped is zeroed when used.
+namespace laq {
+
+constexpr int kSmxRowsPerTile = 16;
+constexpr int kSmxWavesPerBlock = 16;
+
+// first row of the tile requested at r0, clamped into the block's range [.., r_end)
+LAQ_HD int64_t smx_tile_row(int64_t r0, int64_t r_end) { return r0 < r_end ? r0 : r_end - 1; }
+// rows of that tile inside the range
+LAQ_HD int smx_rows_valid(int64_t rb, int64_t r_end) {
+  return (int)(r_end - rb < kSmxRowsPerTile ? r_end - rb : kSmxRowsPerTile);
+}
+// row inside the tile whose data lane l16 loads / whose label the lane's softmax row needs
+LAQ_HD int smx_data_row(int l16, int rows_valid) { return l16 < rows_valid ? l16 : rows_valid - 1; }
+LAQ_HD int smx_label_row(int wave, int lq, int rows_valid) {
+  const int yrow = 4 * (wave & 3) + lq;                         // softmax waves 0..3: rows 4 wave + lq
+  return yrow < rows_valid ? yrow : rows_valid - 1;
+}
+// float offset inside a row of the lane's 16 bytes of chunk `wave`; chunk wave + 16 n lies
+// smx_chunk_step(n) floats further when it is wholly inside the F columns
+LAQ_HD uint32_t smx_lane_col(int wave, int lq) { return 4u * (4u * (uint32_t)wave + (uint32_t)lq); }
+LAQ_HD uint32_t smx_chunk_step(int n) { return 16u * (uint32_t)kSmxWavesPerBlock * (uint32_t)n; }
+// the same for a chunk that may cross column F: its float4 column, or column 0 if the row (nf4r float4
+// long, padding included) ends before it
+LAQ_HD uint32_t smx_ragged_col(int wave, int n, int lq, int nf4r) {
+  uint32_t q = 4u * (uint32_t)(wave + kSmxWavesPerBlock * n) + (uint32_t)lq;
+  q = q < (uint32_t)nf4r ? q : 0u;
+  return 4u * q;
+}
+// tiled copy: byte offset, inside the worker's tiled shard, of chunk `wave` of the tile holding row rb
+// (of chunk 0 for a wave past the tile's last chunk), and of chunk wave + 16 n (the wave's first chunk
+// again if the tile has no such chunk); the lane adds its own 16 l bytes
+LAQ_HD uint32_t smx_tiled_tile_off(int64_t rb, int nchunk, int wave) {
+  return (uint32_t)(rb / kSmxRowsPerTile) * (uint32_t)(nchunk * 1024) + 1024u * (uint32_t)(wave < nchunk ? wave : 0);
+}
+LAQ_HD uint32_t smx_tiled_chunk_off(uint32_t tile_off, int n, int nfull, int wave, int nchunk) {
+  return tile_off + ((n < nfull || wave + kSmxWavesPerBlock * n < nchunk) ? 1024u * (uint32_t)kSmxWavesPerBlock * (uint32_t)n : 0u);
+}
+// kernel instantiation for F columns: chunks per wave (TMAX) and how many of them exist for every wave and
+// hold no column >= F (NFULL); the tiled copy is zero-padded, so all its chunks count as whole
+LAQ_HD void smx_variant(int F, bool tiled, int& tmax, int& nfull) {
+  const int nchunk = (F + 15) / 16;
+  const int whole = (tiled ? nchunk : F / 16) / kSmxWavesPerBlock;
+  if (nchunk <= kSmxWavesPerBlock) { tmax = 1; nfull = whole >= 1 ? 1 : 0; }
+  else if (nchunk <= 2 * kSmxWavesPerBlock) { tmax = 2; nfull = whole >= 2 ? 2 : 1; }
+  else { tmax = 4; nfull = whole >= 4 ? 4 : (whole == 3 ? 3 : 2); }
+}
+// rows per block and number of blocks per worker: one block per CU at most, whole tiles per block
+LAQ_HD int smx_blocks(int n_cu, int M, int64_t N_m, int* rows_per_block) {
+  int64_t want = n_cu / M;
+  if (want < 1) want = 1;
+  const int64_t tiles = (N_m + kSmxRowsPerTile - 1) / kSmxRowsPerTile;
+  if (want > tiles) want = tiles;
+  const int64_t tpb = (tiles + want - 1) / want;
+  *rows_per_block = (int)(tpb * kSmxRowsPerTile);
+  return (int)((tiles + tpb - 1) / tpb);
+}
+
+}  // namespace laq

@@ -694,7 +694,6 @@ int worker_grads(laq_ctx* ctx, const float* theta, float* G) {
   const int kf = (ctx->F + 63) / 64;
   const size_t mfma_lds = softmax_mfma_lds(ctx);
   if (mfma_lds) {
-    const int nchunk = (ctx->F + 15) / 16;
 #define LAQ_SMM(T, NF)                                                                                 \
   do {                                                                                                 \
     auto kfn = ctx->gather_idx ? softmax_grad_mfma_kernel<T, NF, kSrcGather>                           \

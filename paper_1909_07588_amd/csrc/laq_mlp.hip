@@ -14,6 +14,8 @@
 // tile and is bandwidth-bound: plain VALU kernels, one read of the activations.
 #include <math.h>
 
+#include <type_traits>
+
 #include "laq_internal.h"
 #include "laq_tile_loader.h"
 
@@ -126,25 +128,37 @@ __device__ __forceinline__ void store_transposed(float (*tile)[BX + 4], const fl
   }
 }
 
-// Aligned operands: unconditional clamped loads (addresses: FastLoaderAddr in laq_tile_loader.h).
+// Aligned operands: unconditional clamped loads (addresses: FastLoaderAddr in laq_tile_loader.h) through
+// buffer loads whose base is uniform: the K loop advances it with scalar instructions, the lane offsets
+// never change, so no vector instruction is spent on addresses (on a SIMD they take the issue slots the
+// matrix instructions need).  The descriptor's size field is left at its maximum: every address is
+// clamped into the operand by construction (walked on the host), the hardware check is not relied on.
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 template <int BX, int BK, bool XMAJOR>
 struct FastLoader {
   FastLoaderAddr<BX, BK, XMAJOR> at;
+  const float* S;
   static constexpr int NV = FastLoaderAddr<BX, BK, XMAJOR>::NV;
-  __device__ __forceinline__ void init(const float* S, int64_t ld, int K, int X, int x0) {
-    at.init((int)threadIdx.x, S, ld, K, X, x0);
+  __device__ __forceinline__ void init(const float* S_, int64_t ld, int K, int X, int x0) {
+    S = S_;
+    at.init((int)threadIdx.x, ld, K, X, x0);
   }
-  // Loads K tile number `tile` (tiles are requested in order 0, 1, 2, ...) and advances the
-  // pointers.  Nothing here touches the loaded values, so the wave does not wait for them before it
-  // multiplies.
+  static __device__ __forceinline__ float4 load16(const float* base, uint32_t voff) {
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, 0xffffffff, 0x00020000);
+    const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, 0, 0);
+    return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3]));
+  }
+  // Loads K tile number `tile`.  Nothing here touches the loaded values, so the wave does not wait
+  // for them before it multiplies.
   __device__ __forceinline__ void load(int tile, float4 (&r)[NV]) {
     if (at.is_whole(tile)) {                              // uniform
+      const float* base = S + at.base(tile);
 #pragma unroll
-      for (int i = 0; i < NV; ++i) r[i] = *reinterpret_cast<const float4*>(at.whole(i));
-      at.advance();
+      for (int i = 0; i < NV; ++i) r[i] = load16(base, at.voff[i]);
     } else {
+      const float* base = S + at.partial_base(tile);
 #pragma unroll
-      for (int i = 0; i < NV; ++i) r[i] = *reinterpret_cast<const float4*>(at.partial(tile, i));
+      for (int i = 0; i < NV; ++i) r[i] = load16(base, at.partial_voff(tile, i));
     }
   }
   // zeroes what lies outside the operand; called when the registers move to LDS
@@ -237,8 +251,11 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   stage(0, 0);
   __syncthreads();
   const int kh = lane >> 5, li = lane & 31;
-  int cur = 0;
-  for (int k0 = 0; k0 < g.K; k0 += BK) {
+  // One K tile: request the next tile, multiply the current one out of LDS buffer CUR, park the next one
+  // in the other buffer.  CUR is a compile-time constant (the K loop is unrolled by two), so that the
+  // buffers' LDS addresses are immediates.
+  auto tile_step = [&](auto cur_c, int k0) {
+    constexpr int cur = NBUF == 2 ? decltype(cur_c)::value : 0;
     const bool more = k0 + BK < g.K;
     if (more) fetch(k0 + BK);
 #pragma unroll
@@ -258,7 +275,6 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
       // the other buffer was last read before the previous barrier: free to overwrite
       if (more) stage(cur ^ 1, k0 + BK);
       __syncthreads();
-      cur ^= 1;
     } else {
       __syncthreads();
       if (more) {
@@ -266,6 +282,10 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
         __syncthreads();
       }
     }
+  };
+  for (int k0 = 0; k0 < g.K; k0 += 2 * BK) {
+    tile_step(std::integral_constant<int, 0>{}, k0);
+    if (k0 + BK < g.K) tile_step(std::integral_constant<int, 1>{}, k0 + BK);
   }
 
   // epilogue: lane holds C[i][j], j = lane%32, i = 8*(r/4) + 4*(lane/32) + r%4
@@ -747,7 +767,9 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
   const GemmTile t = gemm_tile(ctx, g.M, g.N, batch, big);
   const dim3 grid((unsigned)((g.N + t.bn - 1) / t.bn), (unsigned)((g.M + t.bm - 1) / t.bm), (unsigned)batch);
   // fast loaders need aligned operand rows and no float4 straddling an operand edge
-  const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4;
+  // ... and row strides whose tile offsets fit the loaders' 32-bit lane offsets
+  const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4 &&
+                    g.lda <= ((int64_t)1 << 30) / 224 - 64 && g.ldb <= ((int64_t)1 << 30) / 224 - 64;
   const size_t smem = gemm_lds_bytes(t);
 #define LAQ_GEMM_LAUNCH(KERNEL, P)                                                                            \
   do {                                                                                                        \

@@ -41,24 +41,29 @@ struct TileMap {
 };
 
 // Fast path (operand rows 16-byte aligned, X and K multiples of 4, K >= 4): every float4 is wholly inside
-// or wholly outside the operand, so a lane keeps one clamped source pointer per float4, loads
-// unconditionally and zeroes what lies outside.  No branch sits between the loads and the matrix
-// instructions they overlap.  This struct holds the addressing; the loads themselves are in the kernel.
+// or wholly outside the operand, so a lane loads unconditionally from a clamped place and zeroes what lies
+// outside.  No branch sits between the loads and the matrix instructions they overlap, and no vector
+// instruction computes an address inside the K loop: a lane's float4 lies at
+//     tile origin (uniform: x = x0, k = 0)  +  tile number * kstep (uniform)  +  voff (per lane, constant),
+// which the kernel feeds to a buffer load as a scalar base and a 32-bit lane offset.  This struct holds the
+// addressing (offsets in floats from the operand's first element); the loads themselves are in the kernel.
 template <int BX, int BK, bool XMAJOR>
 struct FastLoaderAddr {
   using TM = TileMap<BX, BK>;
   static constexpr int NV = TM::NV;
-  const float* q[NV];   // source address of this lane's float4 in the next K tile to load (clamped into the operand)
+  uint32_t voff[NV];    // BYTE offset of this lane's float4 of K tile 0 from the tile origin (clamped into the operand)
   int kk[NV];           // its k offset inside the tile
   bool xin[NV];         // its row/column lies inside the operand (false for a float4 that does not exist)
-  int64_t kstep;        // address advance per K tile
-  int64_t kunit;        // address advance per unit of k
+  int64_t origin;       // float offset of the tile origin from the operand's first element
+  int64_t kstep;        // float offset advance per K tile
+  int64_t kunit;        // float offset advance per unit of k
   int K;
   bool all_in;          // the whole block tile lies inside the operand (uniform over the block)
 
-  // S: operand, K-major S[k][x] (XMAJOR false) or X-major S[x][k]; ld: its row stride; the block tile
-  // starts at x0.
-  LAQ_HD void init(int tid, const float* S, int64_t ld, int K_, int X, int x0) {
+  // (Every byte offset the kernel forms -- voff plus one K tile's advance -- must fit 32 bits: the host takes
+  // this path only for row strides up to 2^30 / 224 - 64 floats.)
+  // Operand K-major S[k][x] (XMAJOR false) or X-major S[x][k]; ld: its row stride; the block tile starts at x0.
+  LAQ_HD void init(int tid, int64_t ld, int K_, int X, int x0) {
     K = K_;
     all_in = TM::kExact && x0 + BX <= X;
 #pragma unroll
@@ -67,28 +72,29 @@ struct FastLoaderAddr {
       if (XMAJOR) TM::xmajor(tid, i, kq, xx); else TM::kmajor(tid, i, kq, xx);
       if (!TM::exists(tid, i)) { kq = 0; xx = 0; }
       kk[i] = kq;
-      const int x = x0 + xx;
-      xin[i] = TM::exists(tid, i) && x < X;
-      const int xc = xin[i] ? x : 0;
-      q[i] = XMAJOR ? S + (int64_t)xc * ld + kq : S + (int64_t)kq * ld + xc;
+      xin[i] = TM::exists(tid, i) && x0 + xx < X;
+      const int xr = xin[i] ? xx : 0;                  // a float4 outside the operand reads the tile's first row / column
+      voff[i] = (uint32_t)(4 * (XMAJOR ? (int64_t)xr * ld + kq : (int64_t)kq * ld + xr));
     }
+    origin = XMAJOR ? (int64_t)x0 * ld : (int64_t)x0;
     kstep = XMAJOR ? BK : (int64_t)BK * ld;
     kunit = XMAJOR ? 1 : ld;
   }
-  // Whole K tile `tile` (k0 + BK <= K): the address of float4 i; advance() follows every such tile.
-  LAQ_HD const float* whole(int i) const { return q[i]; }
-  LAQ_HD void advance() {
-#pragma unroll
-    for (int i = 0; i < NV; ++i) q[i] += kstep;
-  }
-  // The last, partial tile (tiles are requested in order 0, 1, 2, ...; `tile` advances were made): a
-  // float4 of k >= K is redirected to k = 0 .. 3 of its own row or column, which is inside the operand
-  // whatever K (its place in tile 0 would not be when K < BK and the first tile is itself the partial one).
-  LAQ_HD const float* partial(int tile, int i) const {
-    const bool kin = tile * BK + kk[i] < K;
-    return kin ? q[i] : q[i] - (int64_t)tile * kstep - kk[i] * kunit;
-  }
   LAQ_HD bool is_whole(int tile) const { return tile * BK + BK <= K; }
+  // Whole K tile `tile`: base (uniform) and the lane's float4
+  LAQ_HD int64_t base(int tile) const { return origin + (int64_t)tile * kstep; }
+  LAQ_HD int64_t whole(int tile, int i) const { return base(tile) + (int64_t)(voff[i] >> 2); }
+  // The last, partial tile.  A float4 of k >= K is redirected to a place that is inside the operand
+  // whatever K: its own place one K tile earlier (a whole tile) when there is one, else (K < BK, the
+  // first tile is itself the partial one) k = 0 .. 3 of its own row or column.  The kernel reads the
+  // partial tile from the base of the tile before it (of tile 0 if there is none) with these lane offsets:
+  LAQ_HD int64_t partial_base(int tile) const { return base(tile >= 1 ? tile - 1 : 0); }
+  LAQ_HD uint32_t partial_voff(int tile, int i) const {
+    const bool kin = tile * BK + kk[i] < K;
+    if (tile >= 1) return kin ? voff[i] + (uint32_t)(4 * kstep) : voff[i];
+    return kin ? voff[i] : voff[i] - (uint32_t)(4 * kk[i] * kunit);
+  }
+  LAQ_HD int64_t partial(int tile, int i) const { return partial_base(tile) + (int64_t)(partial_voff(tile, i) >> 2); }
   // whether float4 i of K tile `tile` holds operand data (else it is zeroed on the way to LDS)
   LAQ_HD bool keep(int tile, int i) const { return (tile * BK + kk[i] < K) && xin[i]; }
 };

@@ -2,7 +2,8 @@
 // (paper_1909_07588_amd/csrc/laq_tile_loader.h, the same functions the kernels compile): for every block
 // tile shape the kernels instantiate, both operand orientations, contraction lengths K and widths X that
 // are multiples of 4 (the fast path's precondition), every tile origin, lane and K tile,
-//   * every address a lane loads 16 bytes from lies inside the operand's span of memory, and
+//   * every address a lane loads 16 bytes from (uniform base + 32-bit lane offset, as the kernel forms it)
+//     lies inside the operand's span of memory, and
 //   * every float4 that is kept (not zeroed on the way to LDS) is the element the tile map says it is.
 // The second half does the same for the softmax-regression kernel's tile loads (row-major, index-list and
 // tiled sources).  Built and run by tests/test_loader_addresses.py; prints the number of addresses checked
@@ -18,22 +19,26 @@ static long long g_checked = 0, g_bad = 0;
 
 template <int BX, int BK, bool XMAJOR>
 static void walk(int X, int K, int64_t ld) {
-  // an operand of K x X (K-major: S[k][x]) or X x K (X-major: S[x][k]) floats with row stride ld
-  float* const S = reinterpret_cast<float*>(static_cast<uintptr_t>(1) << 32);
+  // an operand of K x X (K-major: S[k][x]) or X x K (X-major: S[x][k]) floats with row stride ld; the
+  // loader's offsets are floats from its first element
   const int64_t span = XMAJOR ? (int64_t)(X - 1) * ld + K : (int64_t)(K - 1) * ld + X;   // floats
   using TM = TileMap<BX, BK>;
   const int n_tiles = (K + BK - 1) / BK;
   for (int x0 = 0; x0 < X; x0 += BX) {
     for (int tid = 0; tid < kLoaderThreads; ++tid) {
       FastLoaderAddr<BX, BK, XMAJOR> at;
-      at.init(tid, S, ld, K, X, x0);
+      at.init(tid, ld, K, X, x0);
       for (int tile = 0; tile < n_tiles; ++tile) {
         const bool whole = at.is_whole(tile);
+        // the uniform base the kernel hands to the buffer load lies inside the operand too
+        const int64_t base = whole ? at.base(tile) : at.partial_base(tile);
+        if (base < 0 || base >= span) { ++g_bad; std::printf("violation: base %lld outside span %lld\n", (long long)base, (long long)span); }
         for (int i = 0; i < TM::NV; ++i) {
-          const float* a = whole ? at.whole(i) : at.partial(tile, i);
-          const int64_t off = a - S;
+          const int64_t off = whole ? at.whole(tile, i) : at.partial(tile, i);
+          // the 32-bit lane offset the kernel uses reproduces it
+          const uint32_t v = whole ? at.voff[i] : at.partial_voff(tile, i);
           ++g_checked;
-          bool ok = off >= 0 && off + 3 < span + 0 && (off + 4 <= span);
+          bool ok = off >= 0 && off + 4 <= span && (v & 15u) == 0 && base + (int64_t)(v >> 2) == off;
           if (at.keep(tile, i)) {
             int kk, xx;
             if (XMAJOR) TM::xmajor(tid, i, kk, xx); else TM::kmajor(tid, i, kk, xx);
@@ -50,7 +55,6 @@ static void walk(int X, int K, int64_t ld) {
             ++g_bad;
           }
         }
-        if (whole) at.advance();
       }
     }
   }

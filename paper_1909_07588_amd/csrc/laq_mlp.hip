@@ -251,6 +251,24 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   stage(0, 0);
   __syncthreads();
   const int kh = lane >> 5, li = lane & 31;
+  // This lane's operand elements of k step 0 in buffer 0, one LDS address per 32 x 32 tile.  The
+  // addresses are made opaque to the compiler: from a common base it pairs two reads into one
+  // instruction whose short offsets then need a new base (a vector add) for every k step; from
+  // unrelated bases every read is a single instruction with an immediate offset, and the K loop
+  // holds no vector instruction for LDS addresses (they cost matrix-instruction issue slots).
+  typedef __attribute__((address_space(3))) const float lds_cfloat;
+  lds_cfloat* ap[NLM];
+  lds_cfloat* bp[NLN];
+#pragma unroll
+  for (int i = 0; i < NLM; ++i) {
+    ap[i] = (lds_cfloat*)&As[0][kh][(wy * NLM + i) * 32 + li];
+    asm volatile("" : "+v"(ap[i]));
+  }
+#pragma unroll
+  for (int j = 0; j < NLN; ++j) {
+    bp[j] = (lds_cfloat*)&Bs[0][kh][(wx * NLN + j) * 32 + li];
+    asm volatile("" : "+v"(bp[j]));
+  }
   // One K tile: request the next tile, multiply the current one out of LDS buffer CUR, park the next one
   // in the other buffer.  CUR is a compile-time constant (the K loop is unrolled by two), so that the
   // buffers' LDS addresses are immediates.
@@ -262,9 +280,9 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     for (int kk = 0; kk < BK; kk += 2) {
       float av[NLM], bv[NLN];
 #pragma unroll
-      for (int i = 0; i < NLM; ++i) av[i] = As[cur][kk + kh][(wy * NLM + i) * 32 + li];
+      for (int i = 0; i < NLM; ++i) av[i] = ap[i][(cur * BK + kk) * kLdA];
 #pragma unroll
-      for (int j = 0; j < NLN; ++j) bv[j] = Bs[cur][kk + kh][(wx * NLN + j) * 32 + li];
+      for (int j = 0; j < NLN; ++j) bv[j] = bp[j][(cur * BK + kk) * kLdB];
 #pragma unroll
       for (int i = 0; i < NLM; ++i)
 #pragma unroll

@@ -259,8 +259,8 @@ def run_stress(b, steps, warmup, handover=False):
 def pmc_probe():
     """Short fixed sequence for counter collection under `rocprofv3 --pmc`: a 1 GiB device
     copy (calibrates FETCH_SIZE / WRITE_SIZE against a known size), three iterations of the
-    bandwidth-stress workload at b = 4, twenty iterations of the headline workload, three of
-    the 784-2048-2048-10 network."""
+    bandwidth-stress workload at b = 4, twenty iterations of the multinomial-logistic workload, three of
+    the 784-2048-2048-10 network, five of the 784-200-10 network and of its minibatch variant."""
     import torch
     import laq_synth
     import paper_1909_07588_amd as laq
@@ -285,6 +285,11 @@ def pmc_probe():
     del G
     run_model_workload(laq_synth.workload(2), 20, 2, phase_steps=1)
     run_model_workload(laq_synth.workload(5), 1, 1, phase_steps=1)
+    torch.cuda.empty_cache()
+    run_model_workload(laq_synth.workload(3), 3, 1, phase_steps=1)                  # 784-200-10: wide tiles, split weight gradient
+    ws = laq_synth.workload(3)
+    ws.alpha = 0.008
+    run_model_workload(ws, 3, 1, phase_steps=1, minibatch=500)                     # its minibatch variant: 64 x 64 tiles
     print("pmc probe done", flush=True)
 
 

@@ -327,7 +327,7 @@ def _run_fixed_iterations(w, Xd, yd, theta0, b, force, iters):
 
 
 def modes_table(iters=500):
-    """Table-2-style rows on the headline shapes (synthetic data): the same kernels run as GD
+    """Table-2-style rows on the multinomial-logistic shapes (synthetic data): the same kernels run as GD
     (exact messages, every worker uploads), QGD (Algorithm 1: b-bit messages, every worker
     uploads), LAG (exact messages, skip rule) and LAQ (Algorithm 2), for a fixed number of
     iterations; uploads, transmitted bits and the final alpha^2 ||nabla||^2."""
@@ -346,7 +346,7 @@ def modes_table(iters=500):
 
 
 def sweeps_table(iters=500):
-    """The two sweeps announced at the end of Sec. 4, on the smallest workload and the headline shapes (synthetic data):
+    """The two sweeps announced at the end of Sec. 4, on the smallest workload and the multinomial-logistic shapes (synthetic data):
     LAQ over the number of bits per coordinate, and LAQ beside GD over the level of heterogeneity
     between the workers' shards (laq_synth.heterogeneous); uploads, bits and the final
     alpha^2 ||nabla||^2 after a fixed number of iterations."""
@@ -355,7 +355,7 @@ def sweeps_table(iters=500):
     import paper_1909_07588_amd as laq
     dev = "cuda:0"
     out = []
-    # planted labels and the headline shapes, each at its own step size and at ten times that (the
+    # planted labels and the multinomial-logistic shapes, each at its own step size and at ten times that (the
     # larger steps move the gradients enough for rule (7a) to fire between the forced uploads)
     for cfg, scale_alpha in ((1, 1.0), (1, 10.0), (2, 1.0), (2, 10.0)):
         w = laq_synth.workload(cfg)

@@ -276,18 +276,35 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     constexpr int cur = NBUF == 2 ? decltype(cur_c)::value : 0;
     const bool more = k0 + BK < g.K;
     if (more) fetch(k0 + BK);
+    // the operands of k step s + 1 are requested before the matrix instructions of step s are issued
+    float av[2][NLM], bv[2][NLN];
+#pragma unroll
+    for (int i = 0; i < NLM; ++i) av[0][i] = ap[i][(cur * BK) * kLdA];
+#pragma unroll
+    for (int j = 0; j < NLN; ++j) bv[0][j] = bp[j][(cur * BK) * kLdB];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float av[NLM], bv[NLN];
+      const int s = (kk >> 1) & 1;
+      if (kk + 2 < BK) {
 #pragma unroll
-      for (int i = 0; i < NLM; ++i) av[i] = ap[i][(cur * BK + kk) * kLdA];
+        for (int i = 0; i < NLM; ++i) av[s ^ 1][i] = ap[i][(cur * BK + kk + 2) * kLdA];
 #pragma unroll
-      for (int j = 0; j < NLN; ++j) bv[j] = bp[j][(cur * BK + kk) * kLdB];
+        for (int j = 0; j < NLN; ++j) bv[s ^ 1][j] = bp[j][(cur * BK + kk + 2) * kLdB];
+      }
 #pragma unroll
       for (int i = 0; i < NLM; ++i)
 #pragma unroll
         for (int j = 0; j < NLN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][i], bv[s][j], acc[i][j], 0, 0, 0);
+    }
+    // Instruction order for the scheduler (it would otherwise move every read next to its use to save
+    // registers, and the wave would wait out an LDS latency before each group of matrix instructions):
+    // reads of step 0; then, per step, the reads of the next step followed by this step's matrix instructions.
+    __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      if (kk + 2 < BK) __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, NLM * NLN, 0);
     }
     if (NBUF == 2) {
       // the other buffer was last read before the previous barrier: free to overwrite

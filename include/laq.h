@@ -179,7 +179,10 @@ int laq_worker_grads(laq_ctx* ctx, const float* theta_dev, float* G_dev);
  * rows and the model's scratch for B samples); the data bound by laq_set_data
  * stays bound.  An index outside the shard is clamped and makes
  * laq_get_counters return LAQ_EINVAL.  The radius hand-over to
- * laq_quantize_skip works as for laq_worker_grads.
+ * laq_quantize_skip works as for laq_worker_grads; the block maxima it rests
+ * on lie in ws_dev, which must therefore stay alive and untouched until the
+ * laq_quantize_skip calls on this G_dev have run (or the hand-over is
+ * withdrawn).
  */
 size_t laq_minibatch_workspace_bytes(const laq_ctx* ctx, int64_t B);
 int laq_worker_grads_minibatch(laq_ctx* ctx, const float* theta_dev, const int32_t* idx_dev,

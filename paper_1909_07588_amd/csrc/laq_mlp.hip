@@ -47,6 +47,9 @@ struct GemmArgs {
   // split K (EPI_PARTIAL): blockIdx.z = batch * nsplit + split; split s multiplies rows
   // [s ksplit, min(K, (s+1) ksplit)) of the contraction and stores its product at C + z sC
   int32_t nsplit, ksplit;
+  // first row of block tiles this launch covers (blockIdx.y counts from it): the ragged last row of
+  // tiles can be launched on its own
+  int32_t y0;
 };
 
 // Tile loaders (tile numbering and the aligned loader's addressing: laq_tile_loader.h).
@@ -185,7 +188,9 @@ struct FastLoader {
 // with NLM x NLN matrix-instruction tiles of 32 x 32: block tile 32 WM NLM x 32 WN NLN.
 // NBUF = 2: the next K tile is written to the other LDS buffer while the current one is
 // multiplied (one barrier per tile).
-template <bool TA, bool TB, int EPI, int WM, int NLM, int NLN, bool FAST>
+// RAGGED: an instantiation for blocks on the output's ragged edge: 32 x 32 sub-tiles that lie wholly
+// outside the output take no matrix instructions (their wavefronts still load and stage operands).
+template <bool TA, bool TB, int EPI, int WM, int NLM, int NLN, bool FAST, bool RAGGED = false>
 __device__ __forceinline__ void gemm_body(GemmArgs g) {
   constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
   constexpr int WN = 4 / WM;
@@ -208,9 +213,19 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     B += (int64_t)blockIdx.z * g.sB;
   }
   float* C = g.C + (int64_t)blockIdx.z * g.sC;
-  const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ty = (int)blockIdx.y + g.y0;
+  const int m0 = ty * kBM, n0 = blockIdx.x * kBN;
+  const int lane = threadIdx.x & 63;
+  const int wave = RAGGED ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : (int)(threadIdx.x >> 6);
   const int wy = wave / WN, wx = wave % WN;
+  // sub-tiles of this wavefront that hold any output: the first live_m rows of them by the first live_n columns
+  int live_m = NLM, live_n = NLN;
+  if (RAGGED) {
+    live_m = (g.M - m0 - wy * NLM * 32 + 31) / 32;
+    live_n = (g.N - n0 - wx * NLN * 32 + 31) / 32;
+    live_m = live_m < 0 ? 0 : (live_m > NLM ? NLM : live_m);
+    live_n = live_n < 0 ? 0 : (live_n > NLN ? NLN : live_n);
+  }
 
   floatx16 acc[NLM][NLN];
 #pragma unroll
@@ -276,35 +291,53 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     constexpr int cur = NBUF == 2 ? decltype(cur_c)::value : 0;
     const bool more = k0 + BK < g.K;
     if (more) fetch(k0 + BK);
-    // the operands of k step s + 1 are requested before the matrix instructions of step s are issued
-    float av[2][NLM], bv[2][NLN];
+    if constexpr (RAGGED) {
+      // only the live sub-tiles (uniform conditions); no pipelining, these blocks are few
 #pragma unroll
-    for (int i = 0; i < NLM; ++i) av[0][i] = ap[i][(cur * BK) * kLdA];
+      for (int kk = 0; kk < BK; kk += 2) {
+        float a1[NLM], b1[NLN];
 #pragma unroll
-    for (int j = 0; j < NLN; ++j) bv[0][j] = bp[j][(cur * BK) * kLdB];
+        for (int i = 0; i < NLM; ++i) a1[i] = i < live_m ? ap[i][(cur * BK + kk) * kLdA] : 0.0f;
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      const int s = (kk >> 1) & 1;
-      if (kk + 2 < BK) {
+        for (int j = 0; j < NLN; ++j) b1[j] = j < live_n ? bp[j][(cur * BK + kk) * kLdB] : 0.0f;
 #pragma unroll
-        for (int i = 0; i < NLM; ++i) av[s ^ 1][i] = ap[i][(cur * BK + kk + 2) * kLdA];
+        for (int i = 0; i < NLM; ++i)
 #pragma unroll
-        for (int j = 0; j < NLN; ++j) bv[s ^ 1][j] = bp[j][(cur * BK + kk + 2) * kLdB];
+          for (int j = 0; j < NLN; ++j)
+            if (i < live_m && j < live_n)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[i], b1[j], acc[i][j], 0, 0, 0);
       }
+    } else {
+      // the operands of k step s + 1 are requested before the matrix instructions of step s are issued
+      float av[2][NLM], bv[2][NLN];
 #pragma unroll
-      for (int i = 0; i < NLM; ++i)
+      for (int i = 0; i < NLM; ++i) av[0][i] = ap[i][(cur * BK) * kLdA];
 #pragma unroll
-        for (int j = 0; j < NLN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][i], bv[s][j], acc[i][j], 0, 0, 0);
-    }
-    // Instruction order for the scheduler (it would otherwise move every read next to its use to save
-    // registers, and the wave would wait out an LDS latency before each group of matrix instructions):
-    // reads of step 0; then, per step, the reads of the next step followed by this step's matrix instructions.
-    __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
+      for (int j = 0; j < NLN; ++j) bv[0][j] = bp[j][(cur * BK) * kLdB];
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      if (kk + 2 < BK) __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, NLM * NLN, 0);
+      for (int kk = 0; kk < BK; kk += 2) {
+        const int s = (kk >> 1) & 1;
+        if (kk + 2 < BK) {
+#pragma unroll
+          for (int i = 0; i < NLM; ++i) av[s ^ 1][i] = ap[i][(cur * BK + kk + 2) * kLdA];
+#pragma unroll
+          for (int j = 0; j < NLN; ++j) bv[s ^ 1][j] = bp[j][(cur * BK + kk + 2) * kLdB];
+        }
+#pragma unroll
+        for (int i = 0; i < NLM; ++i)
+#pragma unroll
+          for (int j = 0; j < NLN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][i], bv[s][j], acc[i][j], 0, 0, 0);
+      }
+      // Instruction order for the scheduler (it would otherwise move every read next to its use to save
+      // registers, and the wave would wait out an LDS latency before each group of matrix instructions):
+      // reads of step 0; then, per step, the reads of the next step followed by this step's matrix instructions.
+      __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 2) {
+        if (kk + 2 < BK) __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NLM * NLN, 0);
+      }
     }
     if (NBUF == 2) {
       // the other buffer was last read before the previous barrier: free to overwrite
@@ -364,16 +397,16 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     if (lane == 0) red[wave] = dmax;
     __syncthreads();
     if (threadIdx.x == 0)
-      g.rprod[(int64_t)blockIdx.z * g.rstride + g.rbase + blockIdx.y * gridDim.x + blockIdx.x] =
+      g.rprod[(int64_t)blockIdx.z * g.rstride + g.rbase + ty * gridDim.x + blockIdx.x] =
           max(max(red[0], red[1]), max(red[2], red[3]));
   }
 }
 
 // Square block tiles of 64 NL: 2 x 2 wavefronts.  Four wavefronts per SIMD: 64 accumulator
 // registers + at most 64 others.
-template <bool TA, bool TB, int EPI, int NL, bool FAST>
+template <bool TA, bool TB, int EPI, int NL, bool FAST, bool RAGGED = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_kernel(GemmArgs g) {
-  gemm_body<TA, TB, EPI, 2, NL, NL, FAST>(g);
+  gemm_body<TA, TB, EPI, 2, NL, NL, FAST, RAGGED>(g);
 }
 
 // Layers between 129 and 224 units wide: one 128 x 32 NLN block tile spans the whole width
@@ -812,7 +845,24 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
     else hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, false>), grid, dim3(kThreads), smem, ctx->stream, g);      \
   } while (0)
   if (t.bn == t.bm) {
-    if (t.bm == 128) LAQ_GEMM_LAUNCH(gemm_kernel, 2);
+    if (t.bm == 128) {
+      // A last row of 128 x 128 tiles that holds at most 64 rows of the output (784 rows: 16 in the
+      // seventh) is launched on its own with the instantiation that skips the empty sub-tiles: the
+      // per-worker weight gradients, where that row is a seventh of the work.
+      const int rem = g.M % 128;
+      if constexpr (TA && !TB) if (fast && rem != 0 && rem <= 64) {
+        GemmArgs ge = g;
+        ge.y0 = g.M / 128;
+        if (ge.y0 > 0) {
+          const dim3 gi(grid.x, (unsigned)ge.y0, grid.z);
+          hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), gi, dim3(kThreads), smem, ctx->stream, g);
+        }
+        hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true, true>), dim3(grid.x, 1, grid.z), dim3(kThreads), smem,
+                           ctx->stream, ge);
+        return;
+      }
+      LAQ_GEMM_LAUNCH(gemm_kernel, 2);
+    }
     else LAQ_GEMM_LAUNCH(gemm_kernel, 1);
   } else if (t.bn == 160) {
     LAQ_GEMM_LAUNCH(gemm_wide_kernel, 5);

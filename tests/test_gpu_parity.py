@@ -547,6 +547,23 @@ def test_large_tiles_unsplit_weight_gradient_against_the_oracle():
     check_server(ctx, st, theta, msgs, G)
 
 
+def test_ragged_row_tile_of_the_unsplit_weight_gradient_against_the_oracle():
+    """784 x 1024 weights, 16 workers: 7 x 8 x 16 = 896 tiles of 128 x 128, so the product is not split over
+    the samples and the seventh row tile holds 16 rows of the 128 (three of its four 32-row sub-tiles lie
+    wholly outside the output and take no matrix instructions), as in the first layer of the largest
+    workload.  N_m = 136 leaves a ragged last K tile.  Every worker against the oracle; then codes, radii
+    and decisions from the handed-over block maxima, bit for bit."""
+    dims = (784, 1024, 10)
+    w = laq_synth.Workload("t", 5, laq_synth.KIND_MLP, 16, 136, dims, laq_synth.mlp_param_count(dims), 4)
+    ctx, st, theta, Gd, G, theta_h, X, y = _network_case_with_state(w, 53)
+    G_ref, _ = oracle.grads_all(w.kind, theta_h, X, y, w.dims, w.lam)
+    report = []
+    check_model_grads(w, G, G_ref, theta_h, X, y, report=report)
+    print("relu candidates / flips:", sum(r[1] for r in report), sum(r[2] for r in report))
+    msgs, _ = check_quantize(ctx, st, Gd, G)
+    check_server(ctx, st, theta, msgs, G)
+
+
 def test_planted_near_zero_preactivations_pass_under_the_relu_rule():
     """Twelve hidden units get a bias that cancels one sample's pre-activation to a fraction of a binary32
     ulp: the sign the kernels' binary32 sums give it is arbitrary, and every disagreement with the oracle's

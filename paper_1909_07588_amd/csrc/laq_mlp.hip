@@ -47,9 +47,9 @@ struct GemmArgs {
   // split K (EPI_PARTIAL): blockIdx.z = batch * nsplit + split; split s multiplies rows
   // [s ksplit, min(K, (s+1) ksplit)) of the contraction and stores its product at C + z sC
   int32_t nsplit, ksplit;
-  // first row of block tiles this launch covers (blockIdx.y counts from it): the ragged last row of
-  // tiles can be launched on its own
-  int32_t y0;
+  // first row of block tiles this launch covers (blockIdx.y counts from it) and the radius slot of its
+  // first block: the ragged last rows of the output can be launched on their own, with another tile size
+  int32_t y0, slot0;
 };
 
 // Tile loaders (tile numbering and the aligned loader's addressing: laq_tile_loader.h).
@@ -292,21 +292,25 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     const bool more = k0 + BK < g.K;
     if (more) fetch(k0 + BK);
     if constexpr (RAGGED) {
-      // only the live sub-tiles (uniform conditions); no pipelining, these blocks are few
+      // all operand reads of the K tile first (those of an empty sub-tile stay inside the LDS tile and are
+      // not used), then the matrix instructions of the live sub-tiles only (uniform conditions)
+      float a1[BK / 2][NLM], b1[BK / 2][NLN];
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 2) {
-        float a1[NLM], b1[NLN];
 #pragma unroll
-        for (int i = 0; i < NLM; ++i) a1[i] = i < live_m ? ap[i][(cur * BK + kk) * kLdA] : 0.0f;
+        for (int i = 0; i < NLM; ++i) a1[kk / 2][i] = ap[i][(cur * BK + kk) * kLdA];
 #pragma unroll
-        for (int j = 0; j < NLN; ++j) b1[j] = j < live_n ? bp[j][(cur * BK + kk) * kLdB] : 0.0f;
-#pragma unroll
-        for (int i = 0; i < NLM; ++i)
-#pragma unroll
-          for (int j = 0; j < NLN; ++j)
-            if (i < live_m && j < live_n)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[i], b1[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NLN; ++j) b1[kk / 2][j] = bp[j][(cur * BK + kk) * kLdB];
       }
+#pragma unroll
+      for (int i = 0; i < NLM; ++i)
+#pragma unroll
+        for (int j = 0; j < NLN; ++j)
+          if (i < live_m && j < live_n) {
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 2)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[kk / 2][i], b1[kk / 2][j], acc[i][j], 0, 0, 0);
+          }
     } else {
       // the operands of k step s + 1 are requested before the matrix instructions of step s are issued
       float av[2][NLM], bv[2][NLN];
@@ -397,7 +401,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     if (lane == 0) red[wave] = dmax;
     __syncthreads();
     if (threadIdx.x == 0)
-      g.rprod[(int64_t)blockIdx.z * g.rstride + g.rbase + ty * gridDim.x + blockIdx.x] =
+      g.rprod[(int64_t)blockIdx.z * g.rstride + g.rbase + g.slot0 + blockIdx.y * gridDim.x + blockIdx.x] =
           max(max(red[0], red[1]), max(red[2], red[3]));
   }
 }
@@ -735,6 +739,19 @@ static GemmTile gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch,
   return GemmTile{bt, bt};
 }
 
+// Rows of a per-worker weight gradient past its last full row of 128 x 128 tiles, when they are launched
+// on their own: at most 64 of them (784 rows: 16), in 64 x 64 tiles whose empty 32-row halves take no matrix
+// instructions.  As a seventh row of 128 x 128 tiles they would cost a seventh of the product.
+static int ragged_rows(GemmTile t, int64_t Mr) {
+  const int rem = (int)(Mr % 128);
+  return (t.bm == 128 && t.bn == 128 && rem != 0 && rem <= 64) ? rem : 0;
+}
+// Blocks (= radius slots) of a weight-gradient launch of Mr x Nc outputs per worker
+static int64_t dw_blocks(GemmTile t, int64_t Mr, int64_t Nc) {
+  if (ragged_rows(t, Mr)) return (Mr / 128) * ((Nc + 127) / 128) + (Nc + 63) / 64;
+  return ((Mr + t.bm - 1) / t.bm) * ((Nc + t.bn - 1) / t.bn);
+}
+
 // Weight-gradient GEMMs whose large tiles would leave most CUs idle (narrow layers) split the
 // sample dimension: nsplit partial products per worker, summed by slab_finish_kernel.  All blocks
 // of such a launch are resident at once or nearly so, so the launch takes as long as the
@@ -808,8 +825,7 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
         const int64_t need = (int64_t)ctx->M * ns * in * out;
         splitk = splitk > need ? splitk : need;
       } else {
-        const GemmTile t = gemm_tile(ctx, in, out, ctx->M);
-        cnt += ((out + t.bn - 1) / t.bn) * ((in + t.bm - 1) / t.bm);
+        cnt += dw_blocks(gemm_tile(ctx, in, out, ctx->M), in, out);
       }
     }
     else cnt += (class_len + kThreads - 1) / kThreads;     // class layer, its bias, the last hidden layer's bias
@@ -846,19 +862,21 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
   } while (0)
   if (t.bn == t.bm) {
     if (t.bm == 128) {
-      // A last row of 128 x 128 tiles that holds at most 64 rows of the output (784 rows: 16 in the
-      // seventh) is launched on its own with the instantiation that skips the empty sub-tiles: the
-      // per-worker weight gradients, where that row is a seventh of the work.
-      const int rem = g.M % 128;
-      if constexpr (TA && !TB) if (fast && rem != 0 && rem <= 64) {
-        GemmArgs ge = g;
-        ge.y0 = g.M / 128;
-        if (ge.y0 > 0) {
-          const dim3 gi(grid.x, (unsigned)ge.y0, grid.z);
-          hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), gi, dim3(kThreads), smem, ctx->stream, g);
+      // per-worker weight gradients: the rows past the last full row of tiles go in a launch of their own
+      if constexpr (TA && !TB) if (ragged_rows(t, g.M)) {
+        const int full = g.M / 128;
+        if (full > 0) {
+          const dim3 gi(grid.x, (unsigned)full, grid.z);
+          if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), gi, dim3(kThreads), smem, ctx->stream, g);
+          else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, false>), gi, dim3(kThreads), smem, ctx->stream, g);
         }
-        hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true, true>), dim3(grid.x, 1, grid.z), dim3(kThreads), smem,
-                           ctx->stream, ge);
+        GemmArgs ge = g;
+        ge.y0 = 2 * full;                                   // in rows of 64 x 64 tiles
+        ge.slot0 = full * (int32_t)grid.x;
+        const dim3 gr((unsigned)((g.N + 63) / 64), 1, grid.z);
+        const size_t smem_r = gemm_lds_bytes(GemmTile{64, 64});
+        if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, true, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
+        else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, false, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
         return;
       }
       LAQ_GEMM_LAUNCH(gemm_kernel, 2);
@@ -999,8 +1017,7 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
         rbase += (int32_t)wblocks;
       } else {
         launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
-        const GemmTile t = gemm_tile(ctx, g.M, g.N, ctx->M);
-        rbase += ((g.N + t.bn - 1) / t.bn) * ((g.M + t.bm - 1) / t.bm);
+        rbase += (int32_t)dw_blocks(gemm_tile(ctx, g.M, g.N, ctx->M), g.M, g.N);
       }
     }
     // db_l(m) = column sums of dZ_l(m)   (l = L-1: done with the class layer)

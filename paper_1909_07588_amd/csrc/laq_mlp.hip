@@ -36,8 +36,11 @@ struct GemmArgs {
   int64_t lda, ldb, ldc;
   int64_t sA, sB, sC;  // batch strides (elements) for blockIdx.z
   int32_t vecA, vecB;  // operand rows are 16-byte aligned
-  const float* aux;    // bias[N] | mask[M][ldaux] | W[M][ldaux]
-  int64_t ldaux;
+  const float* aux;    // bias[N] | mask[M][ldaux] (+ blockIdx.z saux) | W[M][ldaux]
+  int64_t ldaux, saux;
+  // EPI_MASK only: column sums of this block's rows of C (the bias gradient's partial sums), at
+  // colpart[(blockIdx.z * gridDim.y + blockIdx.y) * N + column]
+  float* colpart;
   float scale, reg;
   // EPI_GRAD only: stored quantized gradients laid out like C, and where to
   // leave this block's max |C - H| (raw bits): rprod[z * rstride + rbase + block]
@@ -363,6 +366,10 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   // epilogue: lane holds C[i][j], j = lane%32, i = 8*(r/4) + 4*(lane/32) + r%4
   uint32_t dmax = 0;
   const float* Hq = (EPI == EPI_GRAD) ? g.Hq + (int64_t)blockIdx.z * g.sC : nullptr;
+  const float* mask = (EPI == EPI_MASK) ? g.aux + (int64_t)blockIdx.z * g.saux : nullptr;
+  float csum[NLN];
+#pragma unroll
+  for (int tj = 0; tj < NLN; ++tj) csum[tj] = 0.0f;
 #pragma unroll
   for (int ti = 0; ti < NLM; ++ti)
 #pragma unroll
@@ -379,7 +386,8 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
         if (EPI == EPI_BIAS_RELU) {
           v = fmaxf(v + bias, 0.0f);
         } else if (EPI == EPI_MASK) {
-          v = g.aux[(int64_t)row * g.ldaux + col] > 0.0f ? v : 0.0f;
+          v = mask[(int64_t)row * g.ldaux + col] > 0.0f ? v : 0.0f;
+          csum[tj] += v;
         } else if (EPI == EPI_PARTIAL) {
           // plain product of this K range; scale, regulariser and radius follow in the slab sum
         } else {
@@ -390,6 +398,25 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
         C[(int64_t)row * g.ldc + col] = v;
       }
     }
+  if (EPI == EPI_MASK) {
+    // column sums over the block's rows, in a fixed order: the lane's 16 NLM rows above, the other half
+    // of the 32 x 32 tile's rows (lane ^ 32), then the WM wavefront rows through LDS (the A tile's, free
+    // since the K loop's last barrier)
+    float* red = &As[0][0][0];
+#pragma unroll
+    for (int tj = 0; tj < NLN; ++tj) {
+      const float s = csum[tj] + __shfl_xor(csum[tj], 32);
+      if (kh == 0) red[wy * kBN + (wx * NLN + tj) * 32 + li] = s;
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < kBN; c += kThreads) {
+      if (n0 + c >= g.N) break;
+      float s = red[c];
+#pragma unroll
+      for (int w = 1; w < WM; ++w) s += red[w * kBN + c];
+      g.colpart[((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * g.N + n0 + c] = s;
+    }
+  }
   if (EPI == EPI_GRAD) {
     // block maximum of |g - h| for the quantizer's radius (reuses the A tile's LDS)
 #pragma unroll
@@ -697,31 +724,6 @@ __global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __re
     rprod[(int64_t)m * rstride + rbase + blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
-// Bias gradient: column sums of dZ over a slab of rows of worker m.
-__global__ __launch_bounds__(kThreads) void colsum_kernel(const float* __restrict__ dZ, int64_t ld, int64_t N_m,
-                                                          int32_t width, int32_t rows_per_slab,
-                                                          float* __restrict__ part) {
-  const int m = blockIdx.z, slab = blockIdx.y;
-  const int j = blockIdx.x * kThreads + threadIdx.x;
-  const int64_t r0 = (int64_t)m * N_m + (int64_t)slab * rows_per_slab;
-  int64_t r1 = r0 + rows_per_slab;
-  const int64_t rend = (int64_t)(m + 1) * N_m;
-  if (r1 > rend) r1 = rend;
-  if (j >= width) return;
-  // eight rows in flight; partial sums combined in a fixed order
-  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-  int64_t n = r0;
-  for (; n + 8 <= r1; n += 8) {
-    float v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = dZ[(n + u) * ld + j];
-    s0 += v[0]; s1 += v[1]; s2 += v[2]; s3 += v[3];
-    s0 += v[4]; s1 += v[5]; s2 += v[6]; s3 += v[7];
-  }
-  for (; n < r1; ++n) s0 += dZ[n * ld + j];
-  part[((int64_t)m * gridDim.y + slab) * width + j] = (s0 + s1) + (s2 + s3);
-}
-
 // ------------------------------------------------------------------ host side
 
 static inline int64_t align_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
@@ -813,7 +815,15 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   const int64_t class_len = (n.n_layers >= 2 ? Kc : 0) + Kc * Cc + Cc;
   const int64_t part_len = class_len > widest ? class_len : widest;
   pl.part_len = part_len;
-  pl.part_off = off; off += align_up((int64_t)ctx->M * pl.n_slab * part_len, 64);
+  // the same buffer takes the bias-gradient partials of the earlier hidden layers: one row of sums per row
+  // of block tiles of the activation-gradient product
+  int64_t part_floats = (int64_t)ctx->M * pl.n_slab * part_len;
+  for (int l = 1; l < n.n_layers - 1; ++l) {
+    const GemmTile t = gemm_tile(ctx, N_m, n.dims[l], ctx->M);
+    const int64_t need = (int64_t)ctx->M * ((N_m + t.bm - 1) / t.bm) * n.dims[l];
+    part_floats = part_floats > need ? part_floats : need;
+  }
+  pl.part_off = off; off += align_up(part_floats, 64);
   // one radius slot per block of every kernel that writes a segment of G
   int64_t cnt = 0, splitk = 0;
   for (int l = 1; l <= n.n_layers; ++l) {
@@ -979,14 +989,25 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     const int width = n.dims[l];
     if (l < L - 1) {            // (the class layer's kernel has already left dZ_{L-1})
       // dZ_l = (dZ_{l+1} W_{l+1}^T) .* (A_l > 0)
+      // one batch entry per worker, so that no block tile holds rows of two workers: the epilogue also
+      // leaves the column sums of its rows, the partial sums of db_l(m)
       GemmArgs g{};
-      g.A = dZnext; g.lda = n.dims[l + 1];
+      g.A = dZnext; g.lda = n.dims[l + 1]; g.sA = N_m * g.lda;
       g.B = theta + n.offW[l]; g.ldb = n.dims[l + 1];    // W_{l+1}[d_l][d_{l+1}] read as [N][K]
-      g.C = dZl; g.ldc = width;
-      g.M = (int32_t)S; g.N = width; g.K = n.dims[l + 1];
+      g.C = dZl; g.ldc = width; g.sC = N_m * g.ldc;
+      g.M = (int32_t)N_m; g.N = width; g.K = n.dims[l + 1];
       g.vecA = vec_ok(g.A, g.lda); g.vecB = vec_ok(g.B, g.ldb);
-      g.aux = Al; g.ldaux = width;
-      launch_gemm<false, true, EPI_MASK>(ctx, g, 1);
+      g.aux = Al; g.ldaux = width; g.saux = N_m * g.ldaux;
+      g.colpart = part;
+      launch_gemm<false, true, EPI_MASK>(ctx, g, ctx->M);
+      // db_l(m) = sum of those partials, scaled, + regulariser
+      const GemmTile t = gemm_tile(ctx, N_m, width, ctx->M);
+      const int32_t n_rowtiles = (int32_t)((N_m + t.bm - 1) / t.bm);
+      const unsigned bblocks = (unsigned)((width + kThreads - 1) / kThreads);
+      hipLaunchKernelGGL(slab_finish_kernel, dim3(bblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
+                         part, n_rowtiles, (int64_t)width, (int64_t)width, theta + n.offB[l - 1], inv_N, reg,
+                         G + n.offB[l - 1], ctx->H + n.offB[l - 1], ctx->p_stride, rprod, rstride, rbase);
+      rbase += (int32_t)bblocks;
     }
     // dW_l(m) = A_{l-1}(m)^T dZ_l(m), scaled, + regulariser -> G[m][offW_{l-1}]
     {
@@ -1019,18 +1040,6 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
         launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
         rbase += (int32_t)dw_blocks(gemm_tile(ctx, g.M, g.N, ctx->M), g.M, g.N);
       }
-    }
-    // db_l(m) = column sums of dZ_l(m)   (l = L-1: done with the class layer)
-    if (l < L - 1) {
-      const dim3 cg((unsigned)((width + kThreads - 1) / kThreads), (unsigned)pl.n_slab, (unsigned)ctx->M);
-      hipLaunchKernelGGL(colsum_kernel, cg, dim3(kThreads), 0, ctx->stream, dZl, (int64_t)width, N_m, width,
-                         pl.rows_per_slab, part);
-      const unsigned bblocks = (unsigned)((width + kThreads - 1) / kThreads);
-      hipLaunchKernelGGL(slab_finish_kernel, dim3(bblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream,
-                         part, pl.n_slab, (int64_t)width, (int64_t)width, theta + n.offB[l - 1], inv_N, reg,
-                         G + n.offB[l - 1],
-                         ctx->H + n.offB[l - 1], ctx->p_stride, rprod, rstride, rbase);
-      rbase += (int32_t)bblocks;
     }
     dZnext = dZl;
   }

@@ -175,7 +175,7 @@ def model_rooflines(w, ph, traffic):
         flops = 2 * fwd + dA                      # forward + weight gradients + activation gradients
         out["worker_grads"] = _roofline("mfma", flops / (ph[0] * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s",
                                         traffic.get(w.name + ":worker_grads"),
-                                        "gemm_kernel / gemm_wide_kernel (v_mfma_f32_32x32x2_f32) + class_forward_kernel, "
+                                        "gemm_kernel (v_mfma_f32_32x32x2_f32) / gemm_narrow_kernel (v_mfma_f32_16x16x4_f32) + class_forward_kernel, "
                                         "class_grads_kernel, slab_finish_kernel")
     else:
         gb = (x_bytes + 4 * elems + 4 * w.p) / 1e9   # read X once, read theta, write G

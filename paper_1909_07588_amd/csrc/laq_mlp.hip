@@ -24,6 +24,29 @@ namespace laq {
 static_assert(kLoaderThreads == kThreads, "the tile map assumes the matrix kernels' block size");
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// One matrix instruction on an MT x MT output tile: 32 x 32 x 2 (16 accumulator registers per lane; lane
+// = (k = lane / 32, row or column = lane % 32)) or 16 x 16 x 4 (4 registers; k = lane / 16).
+template <int MT> struct MfmaTile;
+template <> struct MfmaTile<32> {
+  typedef floatx16 Acc;
+  static constexpr int kRegs = 16, kStep = 2;
+  static __device__ __forceinline__ Acc mma(float a, float b, Acc c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+  // row inside the tile of accumulator register r of a lane in k group kq
+  static __device__ __forceinline__ int row(int r, int kq) { return 8 * (r / 4) + 4 * kq + (r % 4); }
+};
+template <> struct MfmaTile<16> {
+  typedef floatx4 Acc;
+  static constexpr int kRegs = 4, kStep = 4;
+  static __device__ __forceinline__ Acc mma(float a, float b, Acc c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+  static __device__ __forceinline__ int row(int r, int kq) { return 4 * kq + r; }
+};
+// LDS row stride of a K-major tile BX wide: the lanes of one operand read (64 / MT k groups of MT
+// consecutive floats, one tile row apart) must spread over the 32 banks two by two
+template <int MT> __host__ __device__ constexpr int lds_stride(int BX) {
+  return MT == 32 ? BX + 4 : BX + ((16 - BX % 32) + 32) % 32;
+}
 
 
 enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2, EPI_PARTIAL = 3 };
@@ -82,14 +105,16 @@ __device__ __forceinline__ void load_direct(const float* S, int64_t ld, int K, i
     r[i] = v;
   }
 }
-template <int BX, int BK>
-__device__ __forceinline__ void store_direct(float (*tile)[BX + 4], const float4 (&r)[TileMap<BX, BK>::NV]) {
+// (PRED: only the float4 whose `on` is set are stored)
+template <int BX, int BK, int LD, bool PRED = false>
+__device__ __forceinline__ void store_direct(float (*tile)[LD], const float4 (&r)[TileMap<BX, BK>::NV],
+                                             const bool* on = nullptr) {
   using TM = TileMap<BX, BK>;
 #pragma unroll
   for (int i = 0; i < TM::NV; ++i) {
     int kk, xx;
     TM::kmajor((int)threadIdx.x, i, kk, xx);
-    if (TM::exists((int)threadIdx.x, i)) *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
+    if (TM::exists((int)threadIdx.x, i) && (!PRED || on[i])) *reinterpret_cast<float4*>(&tile[kk][xx]) = r[i];
   }
 }
 
@@ -118,14 +143,15 @@ __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int 
     r[i] = v;
   }
 }
-template <int BX, int BK>
-__device__ __forceinline__ void store_transposed(float (*tile)[BX + 4], const float4 (&r)[TileMap<BX, BK>::NV]) {
+template <int BX, int BK, int LD, bool PRED = false>
+__device__ __forceinline__ void store_transposed(float (*tile)[LD], const float4 (&r)[TileMap<BX, BK>::NV],
+                                                 const bool* on = nullptr) {
   using TM = TileMap<BX, BK>;
 #pragma unroll
   for (int i = 0; i < TM::NV; ++i) {
     int kk, xx;
     TM::xmajor((int)threadIdx.x, i, kk, xx);
-    if (TM::exists((int)threadIdx.x, i)) {
+    if (TM::exists((int)threadIdx.x, i) && (!PRED || on[i])) {
       tile[kk + 0][xx] = r[i].x;
       tile[kk + 1][xx] = r[i].y;
       tile[kk + 2][xx] = r[i].z;
@@ -167,9 +193,12 @@ struct FastLoader {
       for (int i = 0; i < NV; ++i) r[i] = load16(base, at.partial_voff(tile, i));
     }
   }
-  // zeroes what lies outside the operand; called when the registers move to LDS
+  // Zeroes what lies outside the operand; called when the registers move to LDS.  KONLY: only the float4
+  // past the contraction's end in the last, partial K tile (for a kernel that never stores a float4
+  // outside the operand's width and zeroes its LDS cells once, before the K loop).
+  template <bool KONLY = false>
   __device__ __forceinline__ void mask(int tile, float4 (&r)[NV]) const {
-    if (at.all_in && at.is_whole(tile)) return;           // uniform: interior tile, nothing to zero
+    if ((KONLY || at.all_in) && at.is_whole(tile)) return;           // uniform: nothing to zero
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const bool ok = at.keep(tile, i);
@@ -188,17 +217,19 @@ struct FastLoader {
 #endif
 
 // C = op(A) op(B) with a fused epilogue.  Four wavefronts in WM rows and 4 / WM columns, each
-// with NLM x NLN matrix-instruction tiles of 32 x 32: block tile 32 WM NLM x 32 WN NLN.
+// with NLM x NLN matrix-instruction tiles of MT x MT: block tile MT WM NLM x MT WN NLN.
 // NBUF = 2: the next K tile is written to the other LDS buffer while the current one is
 // multiplied (one barrier per tile).
 // RAGGED: an instantiation for blocks on the output's ragged edge: 32 x 32 sub-tiles that lie wholly
 // outside the output take no matrix instructions (their wavefronts still load and stage operands).
-template <bool TA, bool TB, int EPI, int WM, int NLM, int NLN, bool FAST, bool RAGGED = false>
+template <bool TA, bool TB, int EPI, int WM, int NLM, int NLN, bool FAST, bool RAGGED = false, int MT = 32>
 __device__ __forceinline__ void gemm_body(GemmArgs g) {
   constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
   constexpr int WN = 4 / WM;
-  constexpr int kBM = 32 * WM * NLM, kBN = 32 * WN * NLN;
-  constexpr int kLdA = kBM + 4, kLdB = kBN + 4;               // LDS row strides
+  typedef MfmaTile<MT> MM;
+  constexpr int KS = MM::kStep;                               // k per matrix instruction
+  constexpr int kBM = MT * WM * NLM, kBN = MT * WN * NLN;
+  constexpr int kLdA = lds_stride<MT>(kBM), kLdB = lds_stride<MT>(kBN);   // LDS row strides
   constexpr int NVA = TileMap<kBM, BK>::NV, NVB = TileMap<kBN, BK>::NV;
   extern __shared__ __attribute__((aligned(16))) float gemm_smem[];
   float (*As)[BK][kLdA] = reinterpret_cast<float (*)[BK][kLdA]>(gemm_smem);
@@ -224,19 +255,19 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   // sub-tiles of this wavefront that hold any output: the first live_m rows of them by the first live_n columns
   int live_m = NLM, live_n = NLN;
   if (RAGGED) {
-    live_m = (g.M - m0 - wy * NLM * 32 + 31) / 32;
-    live_n = (g.N - n0 - wx * NLN * 32 + 31) / 32;
+    live_m = (g.M - m0 - wy * NLM * MT + MT - 1) / MT;
+    live_n = (g.N - n0 - wx * NLN * MT + MT - 1) / MT;
     live_m = live_m < 0 ? 0 : (live_m > NLM ? NLM : live_m);
     live_n = live_n < 0 ? 0 : (live_n > NLN ? NLN : live_n);
   }
 
-  floatx16 acc[NLM][NLN];
+  typename MM::Acc acc[NLM][NLN];
 #pragma unroll
   for (int i = 0; i < NLM; ++i)
 #pragma unroll
     for (int j = 0; j < NLN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int r = 0; r < MM::kRegs; ++r) acc[i][j][r] = 0.0f;
 
   float4 ra[NVA], rb[NVB];
   FastLoader<kBM, BK, !TA> fa;   // A is [M][K] (row-major in M) unless TA
@@ -256,20 +287,43 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     if (TB) load_transposed<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
     else load_direct<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
   };
+  // 16 x 16 tiles (layers 129 to 224 wide: every block tile crosses the operand's edge, and with fewer
+  // matrix-instruction cycles per K tile the vector instructions that zero the outside cost 8 % of the
+  // issue slots): a float4 outside the operand's width is never stored, its LDS cells are zeroed once.
+  constexpr bool EDGE_ONCE = FAST && MT == 16;
   auto stage = [&](int buf, int k0) {
+    if (EDGE_ONCE) {
+      fa.template mask<true>(k0 / BK, ra);
+      fb.template mask<true>(k0 / BK, rb);
+      if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin); else store_transposed<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin);
+      if (TB) store_transposed<kBN, BK, kLdB, true>(Bs[buf], rb, fb.at.xin); else store_direct<kBN, BK, kLdB, true>(Bs[buf], rb, fb.at.xin);
+      return;
+    }
     if (FAST) {
       fa.mask(k0 / BK, ra);
       fb.mask(k0 / BK, rb);
     }
-    if (TA) store_direct<kBM, BK>(As[buf], ra); else store_transposed<kBM, BK>(As[buf], ra);
-    if (TB) store_transposed<kBN, BK>(Bs[buf], rb); else store_direct<kBN, BK>(Bs[buf], rb);
+    if (TA) store_direct<kBM, BK, kLdA>(As[buf], ra); else store_transposed<kBM, BK, kLdA>(As[buf], ra);
+    if (TB) store_transposed<kBN, BK, kLdB>(Bs[buf], rb); else store_direct<kBN, BK, kLdB>(Bs[buf], rb);
   };
+  if (EDGE_ONCE) {
+    bool offa[NVA], offb[NVB];
+    float4 za[NVA], zb[NVB];
+#pragma unroll
+    for (int i = 0; i < NVA; ++i) { offa[i] = !fa.at.xin[i]; za[i] = make_float4(0.f, 0.f, 0.f, 0.f); }
+#pragma unroll
+    for (int i = 0; i < NVB; ++i) { offb[i] = !fb.at.xin[i]; zb[i] = make_float4(0.f, 0.f, 0.f, 0.f); }
+    for (int buf = 0; buf < NBUF; ++buf) {
+      if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], za, offa); else store_transposed<kBM, BK, kLdA, true>(As[buf], za, offa);
+      if (TB) store_transposed<kBN, BK, kLdB, true>(Bs[buf], zb, offb); else store_direct<kBN, BK, kLdB, true>(Bs[buf], zb, offb);
+    }
+  }
 
   fetch(0);
   stage(0, 0);
   __syncthreads();
-  const int kh = lane >> 5, li = lane & 31;
-  // This lane's operand elements of k step 0 in buffer 0, one LDS address per 32 x 32 tile.  The
+  const int kh = lane / MT, li = lane % MT;
+  // This lane's operand elements of k step 0 in buffer 0, one LDS address per MT x MT tile.  The
   // addresses are made opaque to the compiler: from a common base it pairs two reads into one
   // instruction whose short offsets then need a new base (a vector add) for every k step; from
   // unrelated bases every read is a single instruction with an immediate offset, and the K loop
@@ -279,13 +333,17 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   lds_cfloat* bp[NLN];
 #pragma unroll
   for (int i = 0; i < NLM; ++i) {
-    ap[i] = (lds_cfloat*)&As[0][kh][(wy * NLM + i) * 32 + li];
+    ap[i] = (lds_cfloat*)&As[0][kh][(wy * NLM + i) * MT + li];
     asm volatile("" : "+v"(ap[i]));
   }
 #pragma unroll
   for (int j = 0; j < NLN; ++j) {
-    bp[j] = (lds_cfloat*)&Bs[0][kh][(wx * NLN + j) * 32 + li];
-    asm volatile("" : "+v"(bp[j]));
+    if (MT == 16 && j > 0) {
+      bp[j] = bp[0] + j * MT;      // 16 x 16 tiles: one base, immediate offsets (registers are short there)
+    } else {
+      bp[j] = (lds_cfloat*)&Bs[0][kh][(wx * NLN + j) * MT + li];
+      asm volatile("" : "+v"(bp[j]));
+    }
   }
   // One K tile: request the next tile, multiply the current one out of LDS buffer CUR, park the next one
   // in the other buffer.  CUR is a compile-time constant (the K loop is unrolled by two), so that the
@@ -297,13 +355,13 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     if constexpr (RAGGED) {
       // all operand reads of the K tile first (those of an empty sub-tile stay inside the LDS tile and are
       // not used), then the matrix instructions of the live sub-tiles only (uniform conditions)
-      float a1[BK / 2][NLM], b1[BK / 2][NLN];
+      float a1[BK / KS][NLM], b1[BK / KS][NLN];
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
+      for (int kk = 0; kk < BK; kk += KS) {
 #pragma unroll
-        for (int i = 0; i < NLM; ++i) a1[kk / 2][i] = ap[i][(cur * BK + kk) * kLdA];
+        for (int i = 0; i < NLM; ++i) a1[kk / KS][i] = ap[i][(cur * BK + kk) * kLdA];
 #pragma unroll
-        for (int j = 0; j < NLN; ++j) b1[kk / 2][j] = bp[j][(cur * BK + kk) * kLdB];
+        for (int j = 0; j < NLN; ++j) b1[kk / KS][j] = bp[j][(cur * BK + kk) * kLdB];
       }
 #pragma unroll
       for (int i = 0; i < NLM; ++i)
@@ -311,9 +369,43 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
         for (int j = 0; j < NLN; ++j)
           if (i < live_m && j < live_n) {
 #pragma unroll
-            for (int kk = 0; kk < BK; kk += 2)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[kk / 2][i], b1[kk / 2][j], acc[i][j], 0, 0, 0);
+            for (int kk = 0; kk < BK; kk += KS)
+              acc[i][j] = MM::mma(a1[kk / KS][i], b1[kk / KS][j], acc[i][j]);
           }
+    } else if constexpr (MT == 16) {
+      // One wavefront row of many small tiles (NLM = 1): registers do not allow a second set of operands,
+      // so the column tiles go in two halves and the reads of one half are in flight while the matrix
+      // instructions of the other are issued: [reads: half 2 of step s][multiply half 1][reads: half 1 of
+      // step s + 1][multiply half 2].
+      static_assert(NLM == 1, "16 x 16 tiles: one tile row per wavefront");
+      constexpr int H = (NLN + 1) / 2;
+      float a1[2], b1[NLN];
+      a1[0] = ap[0][(cur * BK) * kLdA];
+#pragma unroll
+      for (int j = 0; j < H; ++j) b1[j] = bp[j][(cur * BK) * kLdB];
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += KS) {
+        const int s = (kk / KS) & 1;
+#pragma unroll
+        for (int j = H; j < NLN; ++j) b1[j] = bp[j][(cur * BK + kk) * kLdB];
+#pragma unroll
+        for (int j = 0; j < H; ++j) acc[0][j] = MM::mma(a1[s], b1[j], acc[0][j]);
+        if (kk + KS < BK) {
+          a1[s ^ 1] = ap[0][(cur * BK + kk + KS) * kLdA];
+#pragma unroll
+          for (int j = 0; j < H; ++j) b1[j] = bp[j][(cur * BK + kk + KS) * kLdB];
+        }
+#pragma unroll
+        for (int j = H; j < NLN; ++j) acc[0][j] = MM::mma(a1[s], b1[j], acc[0][j]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 1 + H, 0);
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += KS) {
+        __builtin_amdgcn_sched_group_barrier(0x100, NLN - H, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, H, 0);
+        if (kk + KS < BK) __builtin_amdgcn_sched_group_barrier(0x100, 1 + H, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NLN - H, 0);
+      }
     } else {
       // the operands of k step s + 1 are requested before the matrix instructions of step s are issued
       float av[2][NLM], bv[2][NLN];
@@ -322,27 +414,27 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
 #pragma unroll
       for (int j = 0; j < NLN; ++j) bv[0][j] = bp[j][(cur * BK) * kLdB];
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        const int s = (kk >> 1) & 1;
-        if (kk + 2 < BK) {
+      for (int kk = 0; kk < BK; kk += KS) {
+        const int s = (kk / KS) & 1;
+        if (kk + KS < BK) {
 #pragma unroll
-          for (int i = 0; i < NLM; ++i) av[s ^ 1][i] = ap[i][(cur * BK + kk + 2) * kLdA];
+          for (int i = 0; i < NLM; ++i) av[s ^ 1][i] = ap[i][(cur * BK + kk + KS) * kLdA];
 #pragma unroll
-          for (int j = 0; j < NLN; ++j) bv[s ^ 1][j] = bp[j][(cur * BK + kk + 2) * kLdB];
+          for (int j = 0; j < NLN; ++j) bv[s ^ 1][j] = bp[j][(cur * BK + kk + KS) * kLdB];
         }
 #pragma unroll
         for (int i = 0; i < NLM; ++i)
 #pragma unroll
           for (int j = 0; j < NLN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][i], bv[s][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = MM::mma(av[s][i], bv[s][j], acc[i][j]);
       }
       // Instruction order for the scheduler (it would otherwise move every read next to its use to save
       // registers, and the wave would wait out an LDS latency before each group of matrix instructions):
       // reads of step 0; then, per step, the reads of the next step followed by this step's matrix instructions.
       __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        if (kk + 2 < BK) __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
+      for (int kk = 0; kk < BK; kk += KS) {
+        if (kk + KS < BK) __builtin_amdgcn_sched_group_barrier(0x100, NLM + NLN, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, NLM * NLN, 0);
       }
     }
@@ -363,7 +455,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     if (k0 + BK < g.K) tile_step(std::integral_constant<int, 1>{}, k0 + BK);
   }
 
-  // epilogue: lane holds C[i][j], j = lane%32, i = 8*(r/4) + 4*(lane/32) + r%4
+  // epilogue: lane holds C[i][j], j = lane % MT, i = MM::row(r, lane / MT)
   uint32_t dmax = 0;
   const float* Hq = (EPI == EPI_GRAD) ? g.Hq + (int64_t)blockIdx.z * g.sC : nullptr;
   const float* mask = (EPI == EPI_MASK) ? g.aux + (int64_t)blockIdx.z * g.saux : nullptr;
@@ -374,13 +466,13 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   for (int ti = 0; ti < NLM; ++ti)
 #pragma unroll
     for (int tj = 0; tj < NLN; ++tj) {
-      const int col = n0 + (wx * NLN + tj) * 32 + li;
+      const int col = n0 + (wx * NLN + tj) * MT + li;
       if (col >= g.N) continue;
       float bias = 0.0f;
       if (EPI == EPI_BIAS_RELU) bias = g.aux[col];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + (wy * NLM + ti) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+      for (int r = 0; r < MM::kRegs; ++r) {
+        const int row = m0 + (wy * NLM + ti) * MT + MM::row(r, kh);
         if (row >= g.M) continue;
         float v = acc[ti][tj][r];
         if (EPI == EPI_BIAS_RELU) {
@@ -399,14 +491,15 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
       }
     }
   if (EPI == EPI_MASK) {
-    // column sums over the block's rows, in a fixed order: the lane's 16 NLM rows above, the other half
-    // of the 32 x 32 tile's rows (lane ^ 32), then the WM wavefront rows through LDS (the A tile's, free
-    // since the K loop's last barrier)
+    // column sums over the block's rows, in a fixed order: the lane's rows above, the tile's other rows
+    // (the other k groups: lane ^ 32, and lane ^ 16 for 16 x 16 tiles), then the WM wavefront rows through
+    // LDS (the A tile's, free since the K loop's last barrier)
     float* red = &As[0][0][0];
 #pragma unroll
     for (int tj = 0; tj < NLN; ++tj) {
-      const float s = csum[tj] + __shfl_xor(csum[tj], 32);
-      if (kh == 0) red[wy * kBN + (wx * NLN + tj) * 32 + li] = s;
+      float s = csum[tj] + __shfl_xor(csum[tj], 32);
+      if (MT == 16) s += __shfl_xor(s, 16);
+      if (kh == 0) red[wy * kBN + (wx * NLN + tj) * MT + li] = s;
     }
     __syncthreads();
     for (int c = threadIdx.x; c < kBN; c += kThreads) {
@@ -440,19 +533,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
   gemm_body<TA, TB, EPI, 2, NL, NL, FAST, RAGGED>(g);
 }
 
-// Layers between 129 and 224 units wide: one 128 x 32 NLN block tile spans the whole width
-// (a 128 x 128 tiling would spend a second, mostly empty tile column on it).  Each wavefront
-// owns 32 rows and all NLN column tiles; two wavefronts per SIMD.
+// Layers between 129 and 224 units wide: one block tile spans the whole width (a 128 x 128 tiling would
+// spend a second, mostly empty tile column on it), on 16 x 16 x 4 matrix instructions: block tile
+// 64 x 16 NLN, each wavefront 16 rows by all NLN column tiles (4 NLN accumulator registers, four
+// wavefronts per SIMD); the width pads to a multiple of 16 (200 -> 208) and 784 rows to 832.  (The same
+// layers on 128 x 32 NLN tiles of 32 x 32 x 2 instructions, 112 accumulators and two wavefronts per SIMD,
+// were 13 % slower: half as many blocks, 224 columns for 200, 896 rows for 784.)
 template <bool TA, bool TB, int EPI, int NLN, bool FAST>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_wide_kernel(GemmArgs g) {
-  gemm_body<TA, TB, EPI, 4, 1, NLN, FAST>(g);
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_narrow_kernel(GemmArgs g) {
+  gemm_body<TA, TB, EPI, 4, 1, NLN, FAST, false, 16>(g);
 }
 
 // ------------------------------------------------------------------ class layer (C <= 16)
 
 constexpr int kCMax = 16;
-
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Class layer forward + loss gradient: Z[16 rows][C] = A[16][K] W[K][C] + b on
 // v_mfma_f32_16x16x4_f32 (classes padded to 16), P = softmax(Z), dZ = P - onehot(y).
@@ -728,14 +822,17 @@ __global__ __launch_bounds__(kThreads) void slab_finish_kernel(const float* __re
 
 static inline int64_t align_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
-struct GemmTile { int bm, bn; };
+struct GemmTile { int bm, bn; int mt = 32; };   // block tile and the matrix-instruction tile it is made of
 
-// Block tile: 128 x 128 when that still gives every CU a few blocks, else 64 x 64; 128 x (160, 192
-// or 224) for an output 129..224 columns wide with enough rows of tiles to occupy the chip.
+// Block tile: 128 x 128 when that still gives every CU a few blocks, else 64 x 64; 64 x (160, 192, 208
+// or 224) of 16 x 16 matrix tiles for an output 129..224 columns wide with enough rows of tiles to occupy
+// the chip.
 // big: the caller fills the chip by other means (split K) and wants the large tiles.
 static GemmTile gemm_tile(const laq_ctx* ctx, int64_t Mr, int64_t Nc, int batch, bool big = false) {
-  if (Nc > 128 && Nc <= 224 && (big || ((Mr + 127) / 128) * batch >= (int64_t)ctx->n_cu))
-    return GemmTile{128, (int)((Nc + 31) / 32 * 32)};
+  if (Nc > 128 && Nc <= 224 && (big || ((Mr + 63) / 64) * batch >= (int64_t)ctx->n_cu)) {
+    const int w = Nc <= 160 ? 160 : (Nc <= 192 ? 192 : (Nc <= 208 ? 208 : 224));
+    return GemmTile{64, w, 16};
+  }
   const int64_t blocks128 = ((Mr + 127) / 128) * ((Nc + 127) / 128) * batch;
   const int bt = (big || blocks128 >= (int64_t)ctx->n_cu * 3) ? 128 : 64;
   return GemmTile{bt, bt};
@@ -853,7 +950,8 @@ size_t mlp_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
 }
 
 static size_t gemm_lds_bytes(GemmTile t) {
-  return (size_t)LAQ_GEMM_NBUF * LAQ_GEMM_BK * (t.bm + 4 + t.bn + 4) * sizeof(float);
+  const int ld = t.mt == 32 ? lds_stride<32>(t.bm) + lds_stride<32>(t.bn) : lds_stride<16>(t.bm) + lds_stride<16>(t.bn);
+  return (size_t)LAQ_GEMM_NBUF * LAQ_GEMM_BK * ld * sizeof(float);
 }
 
 template <bool TA, bool TB, int EPI>
@@ -870,7 +968,12 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
     if (fast) hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, true>), grid, dim3(kThreads), smem, ctx->stream, g);  \
     else hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, false>), grid, dim3(kThreads), smem, ctx->stream, g);      \
   } while (0)
-  if (t.bn == t.bm) {
+  if (t.mt == 16) {
+    if (t.bn == 160) LAQ_GEMM_LAUNCH(gemm_narrow_kernel, 10);
+    else if (t.bn == 192) LAQ_GEMM_LAUNCH(gemm_narrow_kernel, 12);
+    else if (t.bn == 208) LAQ_GEMM_LAUNCH(gemm_narrow_kernel, 13);
+    else LAQ_GEMM_LAUNCH(gemm_narrow_kernel, 14);
+  } else if (t.bn == t.bm) {
     if (t.bm == 128) {
       // per-worker weight gradients: the rows past the last full row of tiles go in a launch of their own
       if constexpr (TA && !TB) if (ragged_rows(t, g.M)) {
@@ -892,12 +995,6 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
       LAQ_GEMM_LAUNCH(gemm_kernel, 2);
     }
     else LAQ_GEMM_LAUNCH(gemm_kernel, 1);
-  } else if (t.bn == 160) {
-    LAQ_GEMM_LAUNCH(gemm_wide_kernel, 5);
-  } else if (t.bn == 192) {
-    LAQ_GEMM_LAUNCH(gemm_wide_kernel, 6);
-  } else {
-    LAQ_GEMM_LAUNCH(gemm_wide_kernel, 7);
   }
 #undef LAQ_GEMM_LAUNCH
 }

@@ -181,6 +181,7 @@ int main() {
   shapes<128>();
   shapes<160>();
   shapes<192>();
+  shapes<208>();
   shapes<224>();
   std::printf("checked %lld addresses, %lld violations\n", g_checked, g_bad);
   return g_bad == 0 && g_smx_bad == 0 ? 0 : 1;

@@ -28,8 +28,9 @@ def _gradients(w, seed):
     return Gd[:, :w.p].cpu().numpy(), theta, X, y
 
 
-@pytest.mark.parametrize("dims,M,N_m", [((36, 200, 160, 10), 8, 4100),     # aligned: fast loaders
-                                        ((37, 190, 150, 7), 8, 4099)])     # ragged: generic loaders
+@pytest.mark.parametrize("dims,M,N_m", [((36, 200, 160, 10), 8, 4100),     # aligned: fast loaders; tiles 208 and 160 wide
+                                        ((37, 190, 150, 7), 8, 4099),      # ragged: generic loaders
+                                        ((48, 224, 176, 10), 8, 2100)])    # tiles 224 and 192 wide, no column past the edge / 16 past it
 def test_many_samples_forward_backward_and_split_weight_gradients(dims, M, N_m):
     w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, M, N_m, dims, laq_synth.mlp_param_count(dims), 8)
     G, theta, X, y = _gradients(w, 21)

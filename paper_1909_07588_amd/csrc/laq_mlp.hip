@@ -53,7 +53,7 @@ enum { EPI_BIAS_RELU = 0, EPI_MASK = 1, EPI_GRAD = 2, EPI_PARTIAL = 3 };
 
 struct GemmArgs {
   const float* A;      // TA ? [K][M] : [M][K]
-  const float* B;      // TB ? [N][K] : [K][N]
+  const float* B;      // [K][N]
   float* C;            // [M][N]
   int32_t M, N, K;
   int64_t lda, ldb, ldc;
@@ -216,13 +216,13 @@ struct FastLoader {
 #define LAQ_GEMM_NBUF 2
 #endif
 
-// C = op(A) op(B) with a fused epilogue.  Four wavefronts in WM rows and 4 / WM columns, each
+// C = op(A) B with a fused epilogue (A: [M][K] or, TA, [K][M]; B: [K][N]).  Four wavefronts in WM rows and 4 / WM columns, each
 // with NLM x NLN matrix-instruction tiles of MT x MT: block tile MT WM NLM x MT WN NLN.
 // NBUF = 2: the next K tile is written to the other LDS buffer while the current one is
 // multiplied (one barrier per tile).
 // RAGGED: an instantiation for blocks on the output's ragged edge: 32 x 32 sub-tiles that lie wholly
 // outside the output take no matrix instructions (their wavefronts still load and stage operands).
-template <bool TA, bool TB, int EPI, int WM, int NLM, int NLN, bool FAST, bool RAGGED = false, int MT = 32>
+template <bool TA, int EPI, int WM, int NLM, int NLN, bool FAST, bool RAGGED = false, int MT = 32>
 __device__ __forceinline__ void gemm_body(GemmArgs g) {
   constexpr int BK = LAQ_GEMM_BK, NBUF = LAQ_GEMM_NBUF;
   constexpr int WN = 4 / WM;
@@ -240,7 +240,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     const int zb = blockIdx.z / g.nsplit, zs = blockIdx.z - zb * g.nsplit;
     const int64_t ks = (int64_t)zs * g.ksplit;
     A += (int64_t)zb * g.sA + (TA ? ks * g.lda : ks);
-    B += (int64_t)zb * g.sB + (TB ? ks : ks * g.ldb);
+    B += (int64_t)zb * g.sB + ks * g.ldb;
     g.K = (int32_t)((int64_t)g.K - ks < g.ksplit ? (int64_t)g.K - ks : g.ksplit);
   } else {
     A += (int64_t)blockIdx.z * g.sA;
@@ -271,7 +271,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
 
   float4 ra[NVA], rb[NVB];
   FastLoader<kBM, BK, !TA> fa;   // A is [M][K] (row-major in M) unless TA
-  FastLoader<kBN, BK, TB> fb;    // B is [N][K] only if TB
+  FastLoader<kBN, BK, false> fb;
   if (FAST) {
     fa.init(A, g.lda, g.K, g.M, m0);
     fb.init(B, g.ldb, g.K, g.N, n0);
@@ -284,8 +284,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     }
     if (TA) load_direct<kBM, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
     else load_transposed<kBM, BK>(A, g.lda, g.K, g.M, k0, m0, g.vecA, ra);
-    if (TB) load_transposed<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
-    else load_direct<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
+    load_direct<kBN, BK>(B, g.ldb, g.K, g.N, k0, n0, g.vecB, rb);
   };
   // 16 x 16 tiles (layers 129 to 224 wide: every block tile crosses the operand's edge, and with fewer
   // matrix-instruction cycles per K tile the vector instructions that zero the outside cost 8 % of the
@@ -296,7 +295,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
       fa.template mask<true>(k0 / BK, ra);
       fb.template mask<true>(k0 / BK, rb);
       if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin); else store_transposed<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin);
-      if (TB) store_transposed<kBN, BK, kLdB, true>(Bs[buf], rb, fb.at.xin); else store_direct<kBN, BK, kLdB, true>(Bs[buf], rb, fb.at.xin);
+      store_direct<kBN, BK, kLdB, true>(Bs[buf], rb, fb.at.xin);
       return;
     }
     if (FAST) {
@@ -304,7 +303,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
       fb.mask(k0 / BK, rb);
     }
     if (TA) store_direct<kBM, BK, kLdA>(As[buf], ra); else store_transposed<kBM, BK, kLdA>(As[buf], ra);
-    if (TB) store_transposed<kBN, BK, kLdB>(Bs[buf], rb); else store_direct<kBN, BK, kLdB>(Bs[buf], rb);
+    store_direct<kBN, BK, kLdB>(Bs[buf], rb);
   };
   if (EDGE_ONCE) {
     bool offa[NVA], offb[NVB];
@@ -315,7 +314,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     for (int i = 0; i < NVB; ++i) { offb[i] = !fb.at.xin[i]; zb[i] = make_float4(0.f, 0.f, 0.f, 0.f); }
     for (int buf = 0; buf < NBUF; ++buf) {
       if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], za, offa); else store_transposed<kBM, BK, kLdA, true>(As[buf], za, offa);
-      if (TB) store_transposed<kBN, BK, kLdB, true>(Bs[buf], zb, offb); else store_direct<kBN, BK, kLdB, true>(Bs[buf], zb, offb);
+      store_direct<kBN, BK, kLdB, true>(Bs[buf], zb, offb);
     }
   }
 
@@ -528,9 +527,9 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
 
 // Square block tiles of 64 NL: 2 x 2 wavefronts.  Four wavefronts per SIMD: 64 accumulator
 // registers + at most 64 others.
-template <bool TA, bool TB, int EPI, int NL, bool FAST, bool RAGGED = false>
+template <bool TA, int EPI, int NL, bool FAST, bool RAGGED = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_kernel(GemmArgs g) {
-  gemm_body<TA, TB, EPI, 2, NL, NL, FAST, RAGGED>(g);
+  gemm_body<TA, EPI, 2, NL, NL, FAST, RAGGED>(g);
 }
 
 // Layers between 129 and 224 units wide: one block tile spans the whole width (a 128 x 128 tiling would
@@ -539,9 +538,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
 // wavefronts per SIMD); the width pads to a multiple of 16 (200 -> 208) and 784 rows to 832.  (The same
 // layers on 128 x 32 NLN tiles of 32 x 32 x 2 instructions, 112 accumulators and two wavefronts per SIMD,
 // were 13 % slower: half as many blocks, 224 columns for 200, 896 rows for 784.)
-template <bool TA, bool TB, int EPI, int NLN, bool FAST>
+template <bool TA, int EPI, int NLN, bool FAST>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_narrow_kernel(GemmArgs g) {
-  gemm_body<TA, TB, EPI, 4, 1, NLN, FAST, false, 16>(g);
+  gemm_body<TA, EPI, 4, 1, NLN, FAST, false, 16>(g);
 }
 
 // ------------------------------------------------------------------ class layer (C <= 16)
@@ -773,6 +772,25 @@ __global__ __launch_bounds__(kThreads) void class_grads_kernel(const float* __re
   if (sums_class) out[kb + (int64_t)K * C + threadIdx.x] = bclass;
 }
 
+// Wt[c][r] = W[r][c] for W of R x Cn floats (rows packed): 32 x 32 tiles through LDS, both sides coalesced.
+__global__ __launch_bounds__(kThreads) void transpose_kernel(const float* __restrict__ W, int32_t Rn, int32_t Cn,
+                                                             float* __restrict__ Wt) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+#pragma unroll
+  for (int i = 0; i < 32; i += 8) {
+    const int r = r0 + ty + i, c = c0 + tx;
+    if (r < Rn && c < Cn) tile[ty + i][tx] = W[(int64_t)r * Cn + c];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 32; i += 8) {
+    const int c = c0 + ty + i, r = r0 + tx;
+    if (r < Rn && c < Cn) Wt[(int64_t)c * Rn + r] = tile[tx][ty + i];
+  }
+}
+
 // G[m][off + j] = (sum over slabs, ascending) part[m][slab][j] * scale + reg * theta[off + j],
 // part rows `stride` floats apart.
 // Also leaves the block maximum of |G - H| (raw bits) in rprod[m * rstride + rbase + blockIdx.x].
@@ -884,6 +902,7 @@ struct MlpPlan {
   int64_t rprod_off;                 // [M][rprod_count] block maxima of |g - h|
   int32_t rprod_count;
   int64_t splitk_off;                // [M][nsplit][in * out] partial weight gradients (largest split layer)
+  int64_t wt_off;                    // transposed copy of the weights an activation-gradient product reads
   int64_t total_floats;
 };
 
@@ -941,6 +960,12 @@ static MlpPlan make_plan(const laq_ctx* ctx, int64_t N_m) {
   pl.rprod_count = (int32_t)cnt;
   pl.rprod_off = off; off += align_up((int64_t)ctx->M * cnt, 64);
   pl.splitk_off = off; off += align_up(splitk, 64);
+  int64_t wt = 0;
+  for (int l = 1; l < n.n_layers - 1; ++l) {
+    const int64_t need = (int64_t)n.dims[l] * n.dims[l + 1];
+    wt = wt > need ? wt : need;
+  }
+  pl.wt_off = off; off += align_up(wt, 64);
   pl.total_floats = off;
   return pl;
 }
@@ -954,7 +979,7 @@ static size_t gemm_lds_bytes(GemmTile t) {
   return (size_t)LAQ_GEMM_NBUF * LAQ_GEMM_BK * ld * sizeof(float);
 }
 
-template <bool TA, bool TB, int EPI>
+template <bool TA, int EPI>
 static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool big = false) {
   const GemmTile t = gemm_tile(ctx, g.M, g.N, batch, big);
   const dim3 grid((unsigned)((g.N + t.bn - 1) / t.bn), (unsigned)((g.M + t.bm - 1) / t.bm), (unsigned)batch);
@@ -965,8 +990,8 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
   const size_t smem = gemm_lds_bytes(t);
 #define LAQ_GEMM_LAUNCH(KERNEL, P)                                                                            \
   do {                                                                                                        \
-    if (fast) hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, true>), grid, dim3(kThreads), smem, ctx->stream, g);  \
-    else hipLaunchKernelGGL((KERNEL<TA, TB, EPI, P, false>), grid, dim3(kThreads), smem, ctx->stream, g);      \
+    if (fast) hipLaunchKernelGGL((KERNEL<TA, EPI, P, true>), grid, dim3(kThreads), smem, ctx->stream, g);  \
+    else hipLaunchKernelGGL((KERNEL<TA, EPI, P, false>), grid, dim3(kThreads), smem, ctx->stream, g);      \
   } while (0)
   if (t.mt == 16) {
     if (t.bn == 160) LAQ_GEMM_LAUNCH(gemm_narrow_kernel, 10);
@@ -976,20 +1001,20 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
   } else if (t.bn == t.bm) {
     if (t.bm == 128) {
       // per-worker weight gradients: the rows past the last full row of tiles go in a launch of their own
-      if constexpr (TA && !TB) if (ragged_rows(t, g.M)) {
+      if constexpr (TA) if (ragged_rows(t, g.M)) {
         const int full = g.M / 128;
         if (full > 0) {
           const dim3 gi(grid.x, (unsigned)full, grid.z);
-          if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, true>), gi, dim3(kThreads), smem, ctx->stream, g);
-          else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 2, false>), gi, dim3(kThreads), smem, ctx->stream, g);
+          if (fast) hipLaunchKernelGGL((gemm_kernel<TA, EPI, 2, true>), gi, dim3(kThreads), smem, ctx->stream, g);
+          else hipLaunchKernelGGL((gemm_kernel<TA, EPI, 2, false>), gi, dim3(kThreads), smem, ctx->stream, g);
         }
         GemmArgs ge = g;
         ge.y0 = 2 * full;                                   // in rows of 64 x 64 tiles
         ge.slot0 = full * (int32_t)grid.x;
         const dim3 gr((unsigned)((g.N + 63) / 64), 1, grid.z);
         const size_t smem_r = gemm_lds_bytes(GemmTile{64, 64});
-        if (fast) hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, true, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
-        else hipLaunchKernelGGL((gemm_kernel<TA, TB, EPI, 1, false, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
+        if (fast) hipLaunchKernelGGL((gemm_kernel<TA, EPI, 1, true, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
+        else hipLaunchKernelGGL((gemm_kernel<TA, EPI, 1, false, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
         return;
       }
       LAQ_GEMM_LAUNCH(gemm_kernel, 2);
@@ -1026,7 +1051,7 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
     g.vecA = vec_ok(g.A, g.lda); g.vecB = vec_ok(g.B, g.ldb);
     g.aux = theta + n.offB[l - 1];
     if (S > 0x7fffffff) return set_error(ctx, LAQ_EINVAL, "MLP: too many samples");
-    launch_gemm<false, false, EPI_BIAS_RELU>(ctx, g, 1);
+    launch_gemm<false, EPI_BIAS_RELU>(ctx, g, 1);
     Ain = g.C; ld_in = g.ldc;
   }
   // ---- class layer forward + softmax cross-entropy: dZ_L = P - Y
@@ -1088,15 +1113,20 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
       // dZ_l = (dZ_{l+1} W_{l+1}^T) .* (A_l > 0)
       // one batch entry per worker, so that no block tile holds rows of two workers: the epilogue also
       // leaves the column sums of its rows, the partial sums of db_l(m)
+      // W_{l+1}[d_l][d_{l+1}] is this product's [N][K] operand; from a transposed copy [K][N] its tile loads
+      // go to LDS as they are (16-byte stores), like the forward product's weights
+      float* Wt = ws + pl.wt_off;
+      hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)((n.dims[l + 1] + 31) / 32), (unsigned)((width + 31) / 32)),
+                         dim3(kThreads), 0, ctx->stream, theta + n.offW[l], width, n.dims[l + 1], Wt);
       GemmArgs g{};
       g.A = dZnext; g.lda = n.dims[l + 1]; g.sA = N_m * g.lda;
-      g.B = theta + n.offW[l]; g.ldb = n.dims[l + 1];    // W_{l+1}[d_l][d_{l+1}] read as [N][K]
+      g.B = Wt; g.ldb = width;
       g.C = dZl; g.ldc = width; g.sC = N_m * g.ldc;
       g.M = (int32_t)N_m; g.N = width; g.K = n.dims[l + 1];
       g.vecA = vec_ok(g.A, g.lda); g.vecB = vec_ok(g.B, g.ldb);
       g.aux = Al; g.ldaux = width; g.saux = N_m * g.ldaux;
       g.colpart = part;
-      launch_gemm<false, true, EPI_MASK>(ctx, g, ctx->M);
+      launch_gemm<false, EPI_MASK>(ctx, g, ctx->M);
       // db_l(m) = sum of those partials, scaled, + regulariser
       const GemmTile t = gemm_tile(ctx, N_m, width, ctx->M);
       const int32_t n_rowtiles = (int32_t)((N_m + t.bm - 1) / t.bm);
@@ -1127,14 +1157,14 @@ int mlp_worker_grads(laq_ctx* ctx, const float* theta, float* G) {
         g.C = sp; g.sC = len;
         g.nsplit = ns;
         g.ksplit = (int32_t)align_up((N_m + ns - 1) / ns, 16);
-        launch_gemm<true, false, EPI_PARTIAL>(ctx, g, ctx->M * ns, true);
+        launch_gemm<true, EPI_PARTIAL>(ctx, g, ctx->M * ns, true);
         const unsigned wblocks = (unsigned)((len + kThreads - 1) / kThreads);
         hipLaunchKernelGGL(slab_finish_kernel, dim3(wblocks, (unsigned)ctx->M), dim3(kThreads), 0, ctx->stream, sp,
                            ns, len, len, theta + n.offW[l - 1], inv_N, reg, G + n.offW[l - 1],
                            ctx->H + n.offW[l - 1], ctx->p_stride, rprod, rstride, rbase);
         rbase += (int32_t)wblocks;
       } else {
-        launch_gemm<true, false, EPI_GRAD>(ctx, g, ctx->M);
+        launch_gemm<true, EPI_GRAD>(ctx, g, ctx->M);
         rbase += (int32_t)dw_blocks(gemm_tile(ctx, g.M, g.N, ctx->M), g.M, g.N);
       }
     }

@@ -143,8 +143,13 @@ __device__ __forceinline__ void load_transposed(const float* S, int64_t ld, int 
     r[i] = v;
   }
 }
-template <int BX, int BK, int LD, bool PRED = false>
-__device__ __forceinline__ void store_transposed(float (*tile)[LD], const float4 (&r)[TileMap<BX, BK>::NV],
+// The LDS image of an operand that arrives X-major keeps the k of a pair (2j, 2j+1) side by side:
+// element (k, x) at ((k / 2) BX + x) 2 + k % 2.  A lane's float4 (four k of one x) goes in as two 8-byte
+// stores instead of four 4-byte ones, the 64 lanes of a matrix-instruction operand read (k and k + 1, or
+// the k groups of a 16 x 16 x 4 instruction, of MT consecutive x) touch consecutive words, and no
+// padding is needed for either.
+template <int BX, int BK, bool PRED = false>
+__device__ __forceinline__ void store_transposed(float* tile, const float4 (&r)[TileMap<BX, BK>::NV],
                                                  const bool* on = nullptr) {
   using TM = TileMap<BX, BK>;
 #pragma unroll
@@ -152,10 +157,8 @@ __device__ __forceinline__ void store_transposed(float (*tile)[LD], const float4
     int kk, xx;
     TM::xmajor((int)threadIdx.x, i, kk, xx);
     if (TM::exists((int)threadIdx.x, i) && (!PRED || on[i])) {
-      tile[kk + 0][xx] = r[i].x;
-      tile[kk + 1][xx] = r[i].y;
-      tile[kk + 2][xx] = r[i].z;
-      tile[kk + 3][xx] = r[i].w;
+      *reinterpret_cast<float2*>(&tile[((kk / 2) * BX + xx) * 2]) = make_float2(r[i].x, r[i].y);
+      *reinterpret_cast<float2*>(&tile[((kk / 2 + 1) * BX + xx) * 2]) = make_float2(r[i].z, r[i].w);
     }
   }
 }
@@ -229,7 +232,9 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   typedef MfmaTile<MT> MM;
   constexpr int KS = MM::kStep;                               // k per matrix instruction
   constexpr int kBM = MT * WM * NLM, kBN = MT * WN * NLN;
-  constexpr int kLdA = lds_stride<MT>(kBM), kLdB = lds_stride<MT>(kBN);   // LDS row strides
+  // LDS floats per k of a tile: a padded row for an operand that arrives K-major, BX for one that arrives
+  // X-major (pair layout, see store_transposed)
+  constexpr int kLdA = TA ? lds_stride<MT>(kBM) : kBM, kLdB = lds_stride<MT>(kBN);
   constexpr int NVA = TileMap<kBM, BK>::NV, NVB = TileMap<kBN, BK>::NV;
   extern __shared__ __attribute__((aligned(16))) float gemm_smem[];
   float (*As)[BK][kLdA] = reinterpret_cast<float (*)[BK][kLdA]>(gemm_smem);
@@ -294,7 +299,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
     if (EDGE_ONCE) {
       fa.template mask<true>(k0 / BK, ra);
       fb.template mask<true>(k0 / BK, rb);
-      if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin); else store_transposed<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin);
+      if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], ra, fa.at.xin); else store_transposed<kBM, BK, true>(&As[buf][0][0], ra, fa.at.xin);
       store_direct<kBN, BK, kLdB, true>(Bs[buf], rb, fb.at.xin);
       return;
     }
@@ -302,7 +307,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
       fa.mask(k0 / BK, ra);
       fb.mask(k0 / BK, rb);
     }
-    if (TA) store_direct<kBM, BK, kLdA>(As[buf], ra); else store_transposed<kBM, BK, kLdA>(As[buf], ra);
+    if (TA) store_direct<kBM, BK, kLdA>(As[buf], ra); else store_transposed<kBM, BK>(&As[buf][0][0], ra);
     store_direct<kBN, BK, kLdB>(Bs[buf], rb);
   };
   if (EDGE_ONCE) {
@@ -313,7 +318,7 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < NVB; ++i) { offb[i] = !fb.at.xin[i]; zb[i] = make_float4(0.f, 0.f, 0.f, 0.f); }
     for (int buf = 0; buf < NBUF; ++buf) {
-      if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], za, offa); else store_transposed<kBM, BK, kLdA, true>(As[buf], za, offa);
+      if (TA) store_direct<kBM, BK, kLdA, true>(As[buf], za, offa); else store_transposed<kBM, BK, true>(&As[buf][0][0], za, offa);
       store_direct<kBN, BK, kLdB, true>(Bs[buf], zb, offb);
     }
   }
@@ -332,7 +337,8 @@ __device__ __forceinline__ void gemm_body(GemmArgs g) {
   lds_cfloat* bp[NLN];
 #pragma unroll
   for (int i = 0; i < NLM; ++i) {
-    ap[i] = (lds_cfloat*)&As[0][kh][(wy * NLM + i) * MT + li];
+    const int ax = (wy * NLM + i) * MT + li;
+    ap[i] = TA ? (lds_cfloat*)&As[0][kh][ax] : (lds_cfloat*)(&As[0][0][0] + ((kh / 2) * kBM + ax) * 2 + kh % 2);
     asm volatile("" : "+v"(ap[i]));
   }
 #pragma unroll
@@ -974,9 +980,10 @@ size_t mlp_workspace_bytes(const laq_ctx* ctx, int64_t N_m) {
   return (size_t)make_plan(ctx, N_m).total_floats * sizeof(float) + 256;
 }
 
-static size_t gemm_lds_bytes(GemmTile t) {
-  const int ld = t.mt == 32 ? lds_stride<32>(t.bm) + lds_stride<32>(t.bn) : lds_stride<16>(t.bm) + lds_stride<16>(t.bn);
-  return (size_t)LAQ_GEMM_NBUF * LAQ_GEMM_BK * ld * sizeof(float);
+static size_t gemm_lds_bytes(GemmTile t, bool ta) {
+  const int lda = !ta ? t.bm : (t.mt == 32 ? lds_stride<32>(t.bm) : lds_stride<16>(t.bm));
+  const int ldb = t.mt == 32 ? lds_stride<32>(t.bn) : lds_stride<16>(t.bn);
+  return (size_t)LAQ_GEMM_NBUF * LAQ_GEMM_BK * (lda + ldb) * sizeof(float);
 }
 
 template <bool TA, int EPI>
@@ -987,7 +994,7 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
   // ... and row strides whose tile offsets fit the loaders' 32-bit lane offsets
   const bool fast = g.vecA && g.vecB && (g.M % 4 == 0) && (g.N % 4 == 0) && (g.K % 4 == 0) && g.K >= 4 &&
                     g.lda <= ((int64_t)1 << 30) / 224 - 64 && g.ldb <= ((int64_t)1 << 30) / 224 - 64;
-  const size_t smem = gemm_lds_bytes(t);
+  const size_t smem = gemm_lds_bytes(t, TA);
 #define LAQ_GEMM_LAUNCH(KERNEL, P)                                                                            \
   do {                                                                                                        \
     if (fast) hipLaunchKernelGGL((KERNEL<TA, EPI, P, true>), grid, dim3(kThreads), smem, ctx->stream, g);  \
@@ -1012,7 +1019,7 @@ static void launch_gemm(const laq_ctx* ctx, const GemmArgs& g, int batch, bool b
         ge.y0 = 2 * full;                                   // in rows of 64 x 64 tiles
         ge.slot0 = full * (int32_t)grid.x;
         const dim3 gr((unsigned)((g.N + 63) / 64), 1, grid.z);
-        const size_t smem_r = gemm_lds_bytes(GemmTile{64, 64});
+        const size_t smem_r = gemm_lds_bytes(GemmTile{64, 64}, TA);
         if (fast) hipLaunchKernelGGL((gemm_kernel<TA, EPI, 1, true, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
         else hipLaunchKernelGGL((gemm_kernel<TA, EPI, 1, false, true>), gr, dim3(kThreads), smem_r, ctx->stream, ge);
         return;

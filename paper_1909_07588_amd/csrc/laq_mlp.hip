@@ -1,17 +1,21 @@
 // Worker gradients of the fully connected ReLU network (supplement,
 // "Simulation details"): forward, softmax cross-entropy, backward, for all M
 // workers at once.  theta = (W_1[d0][d1], b_1[d1], W_2, b_2, ...) is shared, so
-// the forward and the activation-gradient products are single GEMMs over all
-// S = M*N_m samples; only the weight gradients are per worker (a GEMM batched
-// over m, written straight into row m of G with the 1/N scale and the
+// the forward products are single GEMMs over all S = M*N_m samples; the
+// activation gradients and the weight gradients are GEMMs batched over the
+// workers (the first so that its epilogue can leave per-worker bias sums, the
+// second written straight into row m of G with the 1/N scale and the
 // regulariser share (N_m/N) lambda theta applied in the epilogue).
 //
-// Dense products run on the fp32 matrix cores (v_mfma_f32_32x32x2_f32):
-// 128x128 block tile, 16-deep K tile staged through LDS in K-major order so
-// that every MFMA operand fetch is a conflict-free ds_read_b32, 4 wavefronts
-// of 64x64 each, next tile prefetched into registers while the current one is
-// multiplied.  The class layer (C <= 16 columns) is too narrow for a matrix
-// tile and is bandwidth-bound: plain VALU kernels, one read of the activations.
+// Dense products run on the fp32 matrix cores: v_mfma_f32_32x32x2_f32 in
+// 128x128 block tiles (4 wavefronts of 64x64 each) or 64x64 ones on small
+// grids, v_mfma_f32_16x16x4_f32 in 64 x (160..224) tiles for layers that
+// narrow.  16-deep K tiles are staged through two LDS buffers, laid out so
+// that every operand fetch is a conflict-free ds_read_b32 at an immediate
+// offset; the next tile is prefetched into registers while the current one is
+// multiplied.  The class layer (C <= 16 columns) is too narrow for these
+// tiles and is bandwidth-bound: its own kernels, one read of the activations
+// each.
 #include <math.h>
 
 #include <type_traits>
@@ -219,11 +223,11 @@ struct FastLoader {
 #define LAQ_GEMM_NBUF 2
 #endif
 
-// C = op(A) B with a fused epilogue (A: [M][K] or, TA, [K][M]; B: [K][N]).  Four wavefronts in WM rows and 4 / WM columns, each
-// with NLM x NLN matrix-instruction tiles of MT x MT: block tile MT WM NLM x MT WN NLN.
-// NBUF = 2: the next K tile is written to the other LDS buffer while the current one is
-// multiplied (one barrier per tile).
-// RAGGED: an instantiation for blocks on the output's ragged edge: 32 x 32 sub-tiles that lie wholly
+// C = op(A) B with a fused epilogue (A: [M][K] or, TA, [K][M]; B: [K][N]).  Four wavefronts in WM rows
+// and 4 / WM columns, each with NLM x NLN matrix-instruction tiles of MT x MT: block tile
+// MT WM NLM x MT WN NLN.  NBUF = 2: the next K tile is written to the other LDS buffer while the current
+// one is multiplied (one barrier per tile).
+// RAGGED: an instantiation for blocks on the output's ragged edge: MT x MT sub-tiles that lie wholly
 // outside the output take no matrix instructions (their wavefronts still load and stage operands).
 template <bool TA, int EPI, int WM, int NLM, int NLN, bool FAST, bool RAGGED = false, int MT = 32>
 __device__ __forceinline__ void gemm_body(GemmArgs g) {

@@ -18,6 +18,9 @@ paper's formula, and each moves that sample's contribution to the gradient by fa
     difference gives each candidate's coefficient, which must round to 0 or 1; layers are taken
     from the top down and the decided flips' effect on the layers below (a rank-one term each) is
     added to the reference before those layers are fitted.
+  * a fitted subset is taken only if it brings the reference closer to the result under test (a fit on
+    nearly parallel or vanishing effect vectors can round noise to a flip), per column and overall: the
+    empty subset, i.e. the oracle's gradient as it is, is always among the subsets tried;
   * non-candidates are never flipped, and the final comparison is the ordinary one, so a kernel
     error cannot hide behind the rule unless it equals a sum of candidate flips.
 
@@ -107,6 +110,10 @@ def reconcile(g, g_ref, theta, Xm, ym, dims, N_total):
             delta = g[idx] - g_adj[idx]
             c, *_ = np.linalg.lstsq(V, delta, rcond=None)
             take = np.rint(np.clip(c, 0.0, 1.0)).astype(bool)
+            # a fit on nearly parallel or vanishing effect vectors can round noise to a flip: a subset is
+            # taken only if it brings the column closer to the result under test
+            if take.any() and np.abs(delta - V[:, take].sum(axis=1)).max() >= np.abs(delta).max():
+                take[:] = False
             for r, t in zip(rows, take):
                 if t:
                     flips.append((int(r), int(j)))
@@ -141,11 +148,14 @@ def assert_network_gradients_close(g, g_ref, theta, Xm, ym, dims, N_total, tag="
     """The network comparison of every parity test: g against the oracle's g_ref for one worker,
     ||g - g_adj||_inf <= rtol ||g_ref||_inf overall and layer_rtol per parameter block, where g_adj
     is g_ref with the candidate decisions reconciled (see the module docstring)."""
-    g_adj, n_cand, n_flip = reconcile(g, g_ref, theta, Xm, ym, dims, N_total)
-    if report is not None:
-        report.append((tag, n_cand, n_flip))
     g = np.asarray(g, np.float64)
     scale = np.abs(g_ref).max()
+    g_adj, n_cand, n_flip = reconcile(g, g_ref, theta, Xm, ym, dims, N_total)
+    if n_flip and np.abs(g - np.asarray(g_ref, np.float64)).max() <= np.abs(g - g_adj).max():
+        # the empty subset is at least as close as the fitted one: compare with the oracle as it is
+        g_adj, n_flip = np.asarray(g_ref, np.float64), 0
+    if report is not None:
+        report.append((tag, n_cand, n_flip))
     err = np.abs(g - g_adj).max()
     assert err <= rtol * scale, (tag, "overall", err / scale, n_cand, n_flip)
     off = 0

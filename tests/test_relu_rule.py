@@ -37,11 +37,15 @@ def _manual_grad(theta, Xm, ym, dims, lam, N_total, flip=()):
     return g + (len(ym) / N_total) * lam * np.asarray(theta, np.float64)
 
 
-def _planted_case(dims=(20, 16, 12, 5), N_m=40, seed=5):
+def _planted_case(dims=(20, 16, 12, 5), N_m=40, seed=5, twin=None):
     """A one-worker network whose units (l = 1, j = 0..3) and (l = 2, j = 0..2) have a pre-activation
-    within a fraction of a binary32 ulp of zero for one sample each."""
+    within a fraction of a binary32 ulp of zero for one sample each.  twin = (n_src, n_dst): sample n_dst
+    becomes sample n_src scaled by 1 + 2^-22, a second near-zero unit wherever n_src has one in layer 1."""
     w = laq_synth.Workload("t", 3, laq_synth.KIND_MLP, 1, N_m, dims, laq_synth.mlp_param_count(dims), 8)
     X, y, theta0 = laq_synth.model_inputs(w)
+    if twin is not None:
+        X = X.copy()
+        X[0, twin[1]] = X[0, twin[0]] * np.float32(1.0 + 2.0 ** -22)
     rng = np.random.default_rng(seed)
     theta = (theta0 + 0.05 * rng.standard_normal(w.p)).astype(np.float32)
     offW, offB, _ = relu_rule._layout(dims)
@@ -95,6 +99,27 @@ def test_no_flip_is_reported_when_the_decisions_agree():
     g_ref = oracle.grad_worker(w.kind, theta, Xm, ym, w.dims, w.lam, w.N_m)
     g_same = _manual_grad(theta, Xm, ym, w.dims, w.lam, w.N_m).astype(np.float32)
     assert relu_rule.assert_network_gradients_close(g_same, g_ref, theta, Xm, ym, w.dims, w.N_m) == (len(planted), 0)
+
+
+def test_nearly_parallel_candidates_do_not_turn_noise_into_a_flip():
+    """Two candidates of one column whose samples are equal up to a factor 1 + 2^-22: their effect vectors
+    are parallel to 2e-7, and a difference of the size of that gap (far inside the tolerance) is fitted
+    by coefficients of order one (1 and minus the ratio of the two vectors).  Rounded and clipped that reads as one flip, which would move the
+    reference by a whole sample's contribution; the rule must see that the subset does not bring the
+    reference closer and compare with the oracle's gradient as it is."""
+    w, Xm, ym, theta, planted = _planted_case(twin=(3, 30))
+    a, z, W, b = relu_rule.forward64(theta, Xm, w.dims)
+    cands = relu_rule.candidate_units(a, z, W, b, w.dims)
+    assert cands[0][3, 0] and cands[0][30, 0]            # both samples are candidates of unit 0 in layer 1
+    g0 = _manual_grad(theta, Xm, ym, w.dims, w.lam, w.N_m)
+    V1 = _manual_grad(theta, Xm, ym, w.dims, w.lam, w.N_m, [(3, 1, 0)]) - g0
+    V2 = _manual_grad(theta, Xm, ym, w.dims, w.lam, w.N_m, [(30, 1, 0)]) - g0
+    s = (V1 @ V2) / (V2 @ V2)                            # V1 = s V2 up to the gap
+    g = g0 + (V1 - s * V2)                               # a gap of 2e-7 |V1|, nothing more
+    g_ref = g0.copy()
+    assert np.abs(g - g_ref).max() <= 1e-6 * np.abs(g_ref).max() < 1e-2 * np.abs(V1).max()
+    n_cand, n_flip = relu_rule.assert_network_gradients_close(g, g_ref, theta, Xm, ym, w.dims, w.N_m)
+    assert n_flip == 0
 
 
 def test_a_flipped_decision_away_from_zero_is_rejected():
